@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the layer-wise paged KV cache hot path on one MI355X.
+
+One "step" is one pass of the whole path over one batch of synthetic input of the chosen
+workload (default: workload 2, LLaMA-2-7B-shaped, 8 prompts x 2048 tokens, bf16):
+for every layer allocate + map, write K/V, causal prefill attention, and for the offloaded
+layers pack + copy to pinned host memory on a side stream; then reload those layers and run one
+decode step (append one token per sequence per layer, paged decode attention).  Inputs are
+resident in HBM before the timed region starts.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2|3] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+METRIC = "decode paged-attn HBM GB/s; prefill attn TFLOP/s; layer offload/reload GB/s"
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", type=int, default=2, choices=(2, 3))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget for the oracle timing")
+    return ap.parse_args()
+
+
+def causal_flops(lens, Hq, d):
+    return 4.0 * d * Hq * sum(n * (n + 1) / 2 for n in lens)
+
+
+def cpu_baseline(w, seconds: float) -> dict:
+    """The oracle as it stands, timed on the host: paged decode attention of ONE layer of the
+    workload (all sequences, all heads, fp64 accumulators), repeated until ~`seconds` are spent."""
+    from oracle import layerkv_oracle as orc
+    from paper_2410_00428_amd import workloads as wl
+    sh = w.shape
+    lens = [n + 1 for n in w.prompt_lens]
+    nblk = sum(wl.blocks_for(n, sh.block_size) for n in lens)
+    o = orc.LayerKVOracle(1, sh.num_q_heads, sh.num_kv_heads, sh.head_dim, sh.block_size, nblk, sh.dtype)
+    o.pool_reset(wl.free_list_order(w.number, nblk, index=77))
+    rng = np.random.default_rng(wl.SEED_BASE + w.number)
+    # fill the blocks directly with seeded bf16 values (the oracle's own write path is not what is timed)
+    o.pool[:] = wl.normal_tensor(rng, o.pool.shape, w.data_scale, sh.dtype)
+    for s, n in enumerate(lens):
+        o.alloc_layer_blocks(s, 0, n)
+    q = wl.normal_tensor(rng, (len(lens), sh.num_q_heads, sh.head_dim), w.data_scale, sh.dtype)
+    bt = o.padded_block_table(range(len(lens)), 0)
+    threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1))
+    kv_bytes = sum(lens) * sh.token_bytes
+    o.paged_decode_attention(q, bt, lens, threads=threads)  # warm
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        o.paged_decode_attention(q, bt, lens, threads=threads)
+        reps += 1
+        el = time.perf_counter() - t0
+        if el > seconds or reps >= 200:
+            break
+    # a second figure for the contraction: causal prefill on a seeded sample of query rows
+    T = sum(w.prompt_lens)
+    n0 = w.prompt_lens[0]
+    Q1, K1, V1 = (wl.normal_tensor(rng, (n0, h, sh.head_dim), w.data_scale, sh.dtype)
+                  for h in (sh.num_q_heads, sh.num_kv_heads, sh.num_kv_heads))
+    rows = wl.sample_rows(rng, n0, 64)
+    tok = np.repeat(rows, 2)
+    head = np.tile(np.array([0, sh.num_q_heads - 1], dtype=np.int32), len(rows))
+    t1 = time.perf_counter()
+    orc.prefill_attention_rows(Q1, K1, V1, [0, n0], sh.dtype, tok, head, threads=threads)
+    t_rows = time.perf_counter() - t1
+    flops_rows = float(sum(4.0 * sh.head_dim * (r + 1) for r in tok))
+    return {"value": round(kv_bytes * reps / el / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": f"paged decode attention of one layer of workload {w.number} ({len(lens)} seqs x "
+                      f"{sh.num_q_heads} heads, context {lens[0]}, {kv_bytes / 2**20:.0f} MiB KV), fp64 accumulators, "
+                      f"{reps} repetitions in {el:.1f} s",
+            "prefill_tflops": round(flops_rows / t_rows / 1e12, 6),
+            "prefill_sample": f"{len(tok)} sampled causal rows of one {n0}-token prompt"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2410_00428_amd import workloads as wl
+    from paper_2410_00428_amd.engine import LayerKVEngine
+
+    w = wl.workload(args.workload)
+    sh = w.shape
+    L, B = sh.num_layers, len(w.prompt_lens)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    eng = LayerKVEngine(sh, w.pool_blocks, wl.free_list_order(w.number, w.pool_blocks))
+    T = sum(w.prompt_lens)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(wl.SEED_BASE + w.number)
+
+    def randn(*shape):
+        return (torch.randn(*shape, generator=gen, device=dev, dtype=torch.float32) * w.data_scale).to(torch.bfloat16)
+
+    # inputs of every layer resident in HBM before timing (layers get their own tensors so that the
+    # per-layer working set is not served from cache)
+    n_in = L if T * sh.num_q_heads * sh.head_dim * 2 * 3 * L < 64 * 2**30 else 4
+    Qs = [randn(T, sh.num_q_heads, sh.head_dim) for _ in range(n_in)]
+    Ks = [randn(T, sh.num_kv_heads, sh.head_dim) for _ in range(n_in)]
+    Vs = [randn(T, sh.num_kv_heads, sh.head_dim) for _ in range(n_in)]
+    O = torch.empty_like(Qs[0])
+    dq = [randn(B, sh.num_q_heads, sh.head_dim) for _ in range(L)]
+    dk = [randn(B, sh.num_kv_heads, sh.head_dim) for _ in range(L)]
+    dv = [randn(B, sh.num_kv_heads, sh.head_dim) for _ in range(L)]
+    dO = torch.empty_like(dq[0])
+    off_layers = list(w.offload_layers)
+    pinned = {l: [eng.pinned(wl.blocks_for(n, sh.block_size) * sh.block_bytes) for n in w.prompt_lens]
+              for l in off_layers}
+    layer_bytes = sum(wl.blocks_for(n, sh.block_size) for n in w.prompt_lens) * sh.block_bytes
+
+    def step():
+        eng.reset()
+        eng.begin_prompts(w.prompt_lens)
+        for l in range(L):
+            i = l % n_in
+            eng.prefill_layer(l, Qs[i], Ks[i], Vs[i], O, offload_to=pinned.get(l))
+        for l in off_layers:
+            eng.release_offloaded(l)
+        for l in off_layers:
+            eng.reload_layer(l)
+        for st in range(w.decode_steps):
+            for l in range(L):
+                eng.decode_layer(l, dq[l], dk[l], dv[l], dO, step=st)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    eng.timing = True
+    eng.timers.clear()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = eng.elapsed_ms()
+    eng.timing = False
+
+    K = args.steps
+    def total(name):
+        return sum(ms.get(name, [0.0]))
+    def avg(name):
+        v = ms.get(name, [])
+        return sum(v) / len(v) if v else float("nan")
+
+    decode_ctx = [[n + st + 1 for n in w.prompt_lens] for st in range(w.decode_steps)]
+    decode_bytes_per_launch = [sum(c) * sh.token_bytes for c in decode_ctx]
+    decode_bytes_total = sum(decode_bytes_per_launch) * L * K
+    decode_gbs = decode_bytes_total / (total("decode_attention") * 1e-3) / 1e9
+    pf_flops = causal_flops(w.prompt_lens, sh.num_q_heads, sh.head_dim)
+    prefill_tflops = pf_flops / (avg("prefill_attention") * 1e-3) / 1e12
+    write_gbs = 2 * T * sh.token_bytes / (avg("write_kv") * 1e-3) / 1e9
+
+    def span_ms(name):  # first start -> last end of a side-stream activity, per step
+        v = eng.timers.get(name, [])
+        per = len(v) // K if K else 0
+        if not per:
+            return float("nan")
+        return sum(v[i * per][0].elapsed_time(v[i * per + per - 1][1]) for i in range(K)) / K
+    off_ms, rel_ms = span_ms("offload"), span_ms("reload")
+    off_gbs = layer_bytes * len(off_layers) / (off_ms * 1e-3) / 1e9 if off_layers else None
+    rel_gbs = layer_bytes * len(off_layers) / (rel_ms * 1e-3) / 1e9 if off_layers else None
+
+    out = {
+        "metric": METRIC, "value": round(decode_gbs, 2), "unit": "GB/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": round(wall * 1e3 / K, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {w.name} (L={L}, Hq={sh.num_q_heads}, Hkv={sh.num_kv_heads}, "
+                               f"d={sh.head_dim}, block 16, {B} prompts x {w.prompt_lens[0]} tokens, "
+                               f"{len(off_layers)} layers offloaded+reloaded, {w.decode_steps} decode step(s))",
+                   "value_is": "decode paged attention: context KV bytes (K and V once per kv head) / event time "
+                               "of the decode kernels, measured inside the full step"},
+        "components": {
+            "decode_paged_attn_GBps": round(decode_gbs, 2),
+            "decode_frac_of_hbm_peak": round(decode_gbs / HBM_PEAK_GBS, 4),
+            "decode_us_per_layer": round(avg("decode_attention") * 1e3, 2),
+            "prefill_attn_TFLOPs": round(prefill_tflops, 2),
+            "prefill_frac_of_bf16_mfma_peak": round(prefill_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+            "prefill_ms_per_layer": round(avg("prefill_attention"), 4),
+            "write_kv_GBps": round(write_gbs, 2),
+            "write_kv_us_per_layer": round(avg("write_kv") * 1e3, 2),
+            "offload_GBps": None if off_gbs is None else round(off_gbs, 2),
+            "reload_GBps": None if rel_gbs is None else round(rel_gbs, 2),
+            "offload_ms_total": None if off_gbs is None else round(off_ms, 2),
+            "reload_ms_total": None if rel_gbs is None else round(rel_ms, 2),
+        },
+        "roofline": {"kernel": "prefill_bf16_kernel (lkv_prefill_attention)", "bound": "mfma",
+                     "achieved": round(prefill_tflops, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(prefill_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None},
+        "rooflines_other": {
+            "decode": {"bound": "hbm", "achieved": round(decode_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                       "frac": round(decode_gbs / HBM_PEAK_GBS, 4)},
+            "write_kv": {"bound": "hbm", "achieved": round(write_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": round(write_gbs / HBM_PEAK_GBS, 4)},
+        },
+    }
+    eng.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

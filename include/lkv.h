@@ -1,0 +1,199 @@
+/*
+ * lkv -- layer-wise paged KV cache for AMD MI355X (gfx950): C ABI.
+ *
+ * The method (LayerKV, arXiv 2410.00428) makes one LAYER of one request the unit of KV-cache
+ * allocation, residency and host offload (Section 3: layer-wise KV block allocation,
+ * management and offloading).  This library is the data path of that idea:
+ *
+ *   - a single device pool holds the KV blocks of every layer (Section 4: one tensor
+ *     allocated at start-up rather than one per layer), each block belonging to one layer of
+ *     one request (Section 3.2.1);
+ *   - every (request, layer) has its own block table and a residency state, GPU or host
+ *     (Section 3.2.2: the extended block table);
+ *   - keys/values are written into a layer's blocks, prompts are processed with causal
+ *     attention (Section 2.1.1), a layer's blocks are packed and copied to pinned host memory
+ *     on a side stream while compute continues and copied back layer by layer for decoding
+ *     (Sections 3.2.1 and 4), and decoding attends through the layer's block table
+ *     (Sections 2.1.2, 2.2: paged attention over non-contiguous blocks).
+ *
+ * Conventions
+ *   Pointers  "device" = memory of the current HIP device; "host" = ordinary host memory,
+ *             "pinned" = page-locked host memory (hipHostMalloc).  The caller owns every
+ *             buffer it passes; the library owns lkv_ctx, its staging buffers, its split-K
+ *             workspace and its events.  The pool is the caller's if lkv_config.pool is set.
+ *   Streams   `stream` is a hipStream_t passed as void* (NULL = the default stream).  Device
+ *             calls only enqueue work and return; results are ready when the stream reaches
+ *             that point.  Host arrays (block_ids) are consumed before the call returns.
+ *   Errors    every call returns an lkv_status; nothing throws or aborts across the ABI.
+ *             lkv_last_error() gives a text for the last failure on that context.  Arguments
+ *             the host can see (layer range, NULL pointers, counts, ids given as host arrays)
+ *             are validated; indices that live in device memory (slot_mapping, block_table,
+ *             context_lens) are the caller's responsibility: they must lie inside the pool.
+ *   Threads   a context is not thread-safe; use one thread per context or lock outside.
+ *
+ * Storage format of the pool (also the format of an offloaded image)
+ *   e = element size (4 for LKV_F32, 2 for LKV_BF16), tau = 2*num_kv_heads*head_dim*e bytes
+ *   per token per layer, beta = block_size*tau bytes per block.  Block b starts at byte
+ *   b*beta.  Inside a block the order is [kv_head][K then V][token in block][channel]:
+ *     K of token slot (b, o), head h, channel c:  b*beta + h*(2*block_size*head_dim*e)
+ *                                                 + o*head_dim*e + c*e
+ *     V of the same:                              that + block_size*head_dim*e
+ *   A slot number is b*block_size + o.  An offloaded image of ids[0..n) is the n blocks
+ *   verbatim, block ids[i] at byte i*beta.
+ */
+#ifndef LKV_H
+#define LKV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lkv_ctx lkv_ctx;
+
+typedef enum {
+  LKV_OK = 0,
+  LKV_ERR_INVALID_ARG = 1,  /* bad layer, NULL pointer, negative count, id outside the pool ... */
+  LKV_ERR_NO_BLOCKS = 2,    /* the free list cannot cover the allocation; nothing was changed  */
+  LKV_ERR_NOT_RESIDENT = 3, /* the (request, layer) has no blocks in the pool right now        */
+  LKV_ERR_HOST_MEMORY = 4,  /* a host allocation failed                                        */
+  LKV_ERR_DEVICE = 5,       /* a HIP call failed; see lkv_last_error                           */
+  LKV_ERR_UNSUPPORTED = 6   /* shape outside what the kernels are built for                    */
+} lkv_status;
+
+typedef enum { LKV_F32 = 0, LKV_BF16 = 1 } lkv_dtype;
+
+/* residency of one (request, layer), Section 3.2.2 */
+enum { LKV_RES_NONE = 0, LKV_RES_GPU = 1, LKV_RES_HOST = 2 };
+
+/* per-layer events the library records (Section 4: transfers run on their own stream,
+ * concurrently with compute, and are ordered against it per layer) */
+typedef enum {
+  LKV_EV_KV_WRITTEN = 0, /* lkv_write_kv of the layer has been enqueued up to here            */
+  LKV_EV_PACKED = 1,     /* the layer's blocks have been gathered out of the pool: the blocks
+                            may be reused from here on                                         */
+  LKV_EV_OFFLOADED = 2,  /* the device-to-host copy of the layer has finished                  */
+  LKV_EV_RELOADED = 3    /* the layer's blocks are back in the pool                            */
+} lkv_event;
+
+typedef struct {
+  int32_t num_layers;
+  int32_t num_q_heads;
+  int32_t num_kv_heads;     /* must divide num_q_heads; q head h uses kv head h/(Hq/Hkv)      */
+  int32_t head_dim;         /* attention kernels: 64 or 128; head_dim*e must be a multiple of 16 */
+  int32_t block_size;       /* tokens per block; attention kernels: 16                         */
+  int32_t dtype;            /* lkv_dtype                                                       */
+  int64_t num_pool_blocks;  /* layer-blocks in the pool                                        */
+  float softmax_scale;      /* 0 => 1/sqrt(head_dim)                                           */
+  int32_t decode_partition; /* tokens per split-K partition of decode attention (multiple of
+                               64); 0 => library default                                       */
+  void *pool;               /* device, num_pool_blocks*beta bytes, 256-byte aligned, or NULL
+                               to let the library allocate (and free) it                       */
+  int64_t staging_bytes;    /* device staging per transfer direction; 0 => 256 MiB.  A layer
+                               image larger than this is moved in several chunks               */
+} lkv_config;
+
+typedef struct {
+  int64_t write_kv_calls, write_kv_bytes;     /* bytes = tokens written * tau (read + write counted once) */
+  int64_t prefill_calls;
+  int64_t decode_calls;
+  int64_t pack_calls, pack_bytes;             /* bytes gathered out of the pool = bytes sent to host */
+  int64_t unpack_calls, unpack_bytes;
+} lkv_stats;
+
+/* ------------------------------------------------------------------ life cycle */
+/* Creates a context on the current HIP device.  Allocates the pool if cfg->pool is NULL, two
+ * staging buffers and the per-layer events.  All blocks start free in ascending id order. */
+lkv_status lkv_create(const lkv_config *cfg, lkv_ctx **out);
+/* The same context without any device resource: only the logical-state calls below work (a
+ * scheduler process without a GPU can plan with it); device calls return LKV_ERR_DEVICE. */
+lkv_status lkv_create_logical(const lkv_config *cfg, lkv_ctx **out);
+/* Waits for the device, then frees everything the library owns.  NULL is allowed. */
+void lkv_destroy(lkv_ctx *ctx);
+/* Text of the last error on ctx (or of the last failed lkv_create if ctx is NULL). */
+const char *lkv_last_error(const lkv_ctx *ctx);
+/* Device pointer of the pool and its size in bytes (either may be NULL). */
+lkv_status lkv_pool_info(const lkv_ctx *ctx, void **pool, int64_t *bytes, int64_t *block_bytes);
+
+/* ------------------------------------------------------------------ logical state (host only; Sections 3.2.1, 3.2.2)
+ * The free list is a stack.  lkv_pool_reset makes every block free and drops every table;
+ * free_order (host, a permutation of 0..n-1, n = num_pool_blocks) gives the order in which
+ * blocks are handed out: free_order[0] first.  Freeing a table pushes its ids in table order,
+ * so the table's last block is the next one handed out. */
+lkv_status lkv_pool_reset(lkv_ctx *ctx, const int32_t *free_order, int64_t n);
+/* Grows the table of (seq, layer) to ceil(num_tokens_total/block_size) blocks (never shrinks)
+ * and marks the layer GPU-resident.  For a host-resident layer this is the reload's
+ * allocation: fresh ids, not the old ones.  LKV_ERR_NO_BLOCKS leaves everything unchanged. */
+lkv_status lkv_alloc_layer_blocks(lkv_ctx *ctx, int64_t seq, int32_t layer, int64_t num_tokens_total);
+/* Returns the blocks of (seq, layer) to the free list.  to_host != 0 records that the layer now
+ * lives on the host (after an offload); 0 forgets the layer.  The caller must have ordered the
+ * release after LKV_EV_PACKED of the data it still needs. */
+lkv_status lkv_free_layer_blocks(lkv_ctx *ctx, int64_t seq, int32_t layer, int32_t to_host);
+/* A finished request releases all its layers, lowest layer first (Section 2.2). */
+lkv_status lkv_free_seq(lkv_ctx *ctx, int64_t seq);
+/* Copies the table of (seq, layer) to out (host, capacity cap entries); *n = its length. */
+lkv_status lkv_get_block_table(const lkv_ctx *ctx, int64_t seq, int32_t layer, int32_t *out, int64_t cap, int64_t *n);
+/* out[i] (host) = slot of token position pos0+i of (seq, layer): table[p/bs]*bs + p%bs. */
+lkv_status lkv_build_slot_mapping(const lkv_ctx *ctx, int64_t seq, int32_t layer, int64_t pos0, int64_t count, int64_t *out);
+lkv_status lkv_layer_residency(const lkv_ctx *ctx, int64_t seq, int32_t layer, int32_t *out);
+int64_t lkv_num_free_blocks(const lkv_ctx *ctx);
+/* Which layers keep their KV on the GPU when x of num_layers are retained: spread evenly,
+ * mask[l] = 1 (host array of num_layers entries) for retained layers.  For 8 layers and x = 4
+ * the retained layers are 1,3,5,7 (the example of Section 3.2.2). */
+lkv_status lkv_plan_retained_layers(int32_t num_layers, int32_t x, int32_t *mask);
+
+/* ------------------------------------------------------------------ device hot path */
+/* K, V: device, [num_tokens][num_kv_heads][head_dim], contiguous.  slot_mapping: device,
+ * int64[num_tokens]; token t goes to slot slot_mapping[t]; a negative slot skips the token.
+ * Waits (on `stream`) for LKV_EV_RELOADED of the layer, then records LKV_EV_KV_WRITTEN of
+ * `layer` on `stream`.  (Sections 2.1.1, 3.2.1) */
+lkv_status lkv_write_kv(lkv_ctx *ctx, int32_t layer, const void *K, const void *V,
+                        const int64_t *slot_mapping, int64_t num_tokens, void *stream);
+
+/* Softmax attention over packed variable-length prompts (Section 2.1.1).  Q, O: device,
+ * [T][num_q_heads][head_dim]; K, V: device, [T][num_kv_heads][head_dim]; cu_seqlens: device,
+ * int32[num_seqs+1], sequence s is tokens cu[s]..cu[s+1].  Row i of a sequence sees keys
+ * 0..i if causal != 0, all keys otherwise.  max_seqlen >= the longest sequence (sizes the
+ * grid).  total_tokens = T (host-known, = cu[num_seqs]).  `layer` selects no data; it names
+ * the layer whose compute this is, for the statistics.  bf16: fp32 accumulation, probabilities
+ * rounded to bf16 before the value product; f32: fp32 throughout. */
+lkv_status lkv_prefill_attention(lkv_ctx *ctx, int32_t layer, const void *Q, const void *K, const void *V,
+                                 void *O, const int32_t *cu_seqlens, int32_t num_seqs,
+                                 int32_t max_seqlen, int64_t total_tokens, int32_t causal, void *stream);
+
+/* Offload image of one layer (Sections 3.2.1, 4): waits (on `stream`) for LKV_EV_KV_WRITTEN of
+ * the layer, gathers blocks block_ids[0..n) (host array) into device staging and copies them to
+ * pinned_dst (n*beta bytes), all on `stream`; records LKV_EV_PACKED after the last gather and
+ * LKV_EV_OFFLOADED after the last copy.  Does not touch tables or the free list. */
+lkv_status lkv_pack_layer_blocks(lkv_ctx *ctx, int32_t layer, const int32_t *block_ids, int64_t n,
+                                 void *pinned_dst, void *stream);
+/* Reload (Section 4: layer by layer, host to device): copies n*beta bytes from pinned_src into
+ * device staging and scatters chunk i into block block_ids[i] -- the ids need not be the ones
+ * the image was packed from.  Records LKV_EV_RELOADED of the layer on `stream`. */
+lkv_status lkv_unpack_layer_blocks(lkv_ctx *ctx, int32_t layer, const int32_t *block_ids, int64_t n,
+                                   const void *pinned_src, void *stream);
+
+/* Decode attention through this layer's block table (Sections 2.1.2, 2.2, 3.2.2).  Q, O:
+ * device, [num_seqs][num_q_heads][head_dim]; block_table: device, int32[num_seqs][max_blocks_per_seq]
+ * (entries past ceil(context_len/bs) are ignored); context_lens: device, int32[num_seqs];
+ * sequence s attends to positions 0..context_lens[s]-1; a zero context gives a zero row.
+ * Waits (on `stream`) for LKV_EV_RELOADED of the layer.  Long contexts are split into
+ * partitions whose partial results are merged by a second kernel; the split-K workspace is
+ * grown with hipMalloc when a call needs more than any earlier one. */
+lkv_status lkv_paged_decode_attention(lkv_ctx *ctx, int32_t layer, const void *Q, void *O,
+                                      const int32_t *block_table, int32_t max_blocks_per_seq,
+                                      const int32_t *context_lens, int32_t num_seqs, void *stream);
+
+/* ------------------------------------------------------------------ ordering and statistics */
+/* Makes `stream` wait for the last recorded event `ev` of `layer` (no-op if never recorded). */
+lkv_status lkv_stream_wait_event(lkv_ctx *ctx, int32_t layer, int32_t ev, void *stream);
+/* Blocks the host until that event has happened. */
+lkv_status lkv_event_synchronize(lkv_ctx *ctx, int32_t layer, int32_t ev);
+/* Copies min(size, sizeof(lkv_stats)) bytes of counters to out (host). */
+lkv_status lkv_get_stats(const lkv_ctx *ctx, lkv_stats *out, int64_t size);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LKV_H */

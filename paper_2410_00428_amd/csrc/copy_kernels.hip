@@ -1,0 +1,135 @@
+// Bandwidth-bound byte movers of the layer-wise KV cache: scatter of new keys/values into a
+// layer's blocks (paper Sections 2.1.1 and 3.2.1) and gather/scatter of whole blocks between
+// the pool and a contiguous staging buffer for host offload and reload (Sections 3.2.1, 4).
+//
+// All three move 16 bytes per lane per access, with the 16 lanes of a 256-byte row (or the
+// 64 lanes of a 1 KiB stretch of a block) adjacent, so every wavefront access is a run of
+// whole cache lines on both sides.  Each thread issues kUnroll independent loads before its
+// stores so that enough bytes are in flight to cover HBM latency.
+#include "lkv_internal.hpp"
+
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+constexpr int kThreads = 256;
+constexpr int kUnroll = 4;
+
+struct Div {  // x / d and x % d; shift >= 0 marks a power of two
+  uint32_t d;
+  int32_t shift;
+};
+__host__ Div make_div(int64_t d) {
+  Div r{(uint32_t)d, -1};
+  if ((d & (d - 1)) == 0) {
+    r.shift = 0;
+    while (((int64_t)1 << r.shift) < d) ++r.shift;
+  }
+  return r;
+}
+__device__ __forceinline__ void divmod(int64_t x, Div dv, int64_t &q, uint32_t &r) {
+  if (dv.shift >= 0) {
+    q = x >> dv.shift;
+    r = (uint32_t)x & (dv.d - 1);
+  } else {
+    q = x / dv.d;
+    r = (uint32_t)(x - q * dv.d);
+  }
+}
+
+// One 16-byte piece per (token, K|V, kv head, piece-in-row).
+__global__ void __launch_bounds__(kThreads)
+write_kv_kernel(const char *__restrict__ K, const char *__restrict__ V, const int64_t *__restrict__ slots,
+                char *__restrict__ pool, int64_t total_pieces, Div pieces_per_row, Div heads, Div block_size,
+                int64_t row_bytes, int64_t block_bytes) {
+  int64_t base = ((int64_t)blockIdx.x * kUnroll) * kThreads + threadIdx.x;
+  u32x4 val[kUnroll];
+  int64_t dst[kUnroll];
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    int64_t i = base + (int64_t)u * kThreads;
+    dst[u] = -1;
+    if (i >= total_pieces) continue;
+    int64_t row, t2, t, blk;
+    uint32_t piece, h, kv, off;
+    divmod(i, pieces_per_row, row, piece);
+    divmod(row, heads, t2, h);
+    kv = (uint32_t)t2 & 1;
+    t = t2 >> 1;
+    int64_t slot = slots[t];
+    if (slot < 0) continue;
+    divmod(slot, block_size, blk, off);
+    const char *src = (kv ? V : K) + (t * heads.d + h) * row_bytes + (int64_t)piece * 16;
+    val[u] = __builtin_nontemporal_load((const u32x4 *)src);
+    dst[u] = blk * block_bytes + ((int64_t)h * 2 + kv) * block_size.d * row_bytes + (int64_t)off * row_bytes +
+             (int64_t)piece * 16;
+  }
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u)
+    if (dst[u] >= 0) *(u32x4 *)(pool + dst[u]) = val[u];
+}
+
+// GATHER: staging[i*beta + o] = pool[ids[i]*beta + o];  !GATHER: the inverse.
+template <bool GATHER>
+__global__ void __launch_bounds__(kThreads)
+move_blocks_kernel(char *__restrict__ pool, char *__restrict__ staging, const int32_t *__restrict__ ids,
+                   int64_t total_pieces, Div pieces_per_block, int64_t block_bytes) {
+  int64_t base = ((int64_t)blockIdx.x * kUnroll) * kThreads + threadIdx.x;
+  u32x4 val[kUnroll];
+  int64_t dst[kUnroll];
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    int64_t i = base + (int64_t)u * kThreads;
+    dst[u] = -1;
+    if (i >= total_pieces) continue;
+    int64_t b;
+    uint32_t piece;
+    divmod(i, pieces_per_block, b, piece);
+    int64_t in_pool = (int64_t)ids[b] * block_bytes + (int64_t)piece * 16;
+    int64_t in_staging = i * 16;
+    if (GATHER) {
+      val[u] = __builtin_nontemporal_load((const u32x4 *)(pool + in_pool));
+      dst[u] = in_staging;
+    } else {
+      val[u] = __builtin_nontemporal_load((const u32x4 *)(staging + in_staging));
+      dst[u] = in_pool;
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u)
+    if (dst[u] >= 0) __builtin_nontemporal_store(val[u], (u32x4 *)((GATHER ? staging : pool) + dst[u]));
+}
+
+unsigned grid_for(int64_t pieces) { return (unsigned)((pieces + (int64_t)kThreads * kUnroll - 1) / ((int64_t)kThreads * kUnroll)); }
+
+}  // namespace
+
+namespace lkv {
+
+hipError_t launch_write_kv(const lkv_ctx *c, const void *K, const void *V, const int64_t *slots, int64_t num_tokens,
+                           hipStream_t s) {
+  int64_t pieces_per_row = c->row_bytes / 16;
+  int64_t total = num_tokens * 2 * c->cfg.num_kv_heads * pieces_per_row;
+  if (total == 0) return hipSuccess;
+  hipLaunchKernelGGL(write_kv_kernel, dim3(grid_for(total)), dim3(kThreads), 0, s, (const char *)K, (const char *)V,
+                     slots, c->pool, total, make_div(pieces_per_row), make_div(c->cfg.num_kv_heads),
+                     make_div(c->cfg.block_size), c->row_bytes, c->block_bytes);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_blocks(const lkv_ctx *c, const int32_t *ids_dev, int64_t n, char *dst, hipStream_t s) {
+  int64_t total = n * (c->block_bytes / 16);
+  if (total == 0) return hipSuccess;
+  hipLaunchKernelGGL(move_blocks_kernel<true>, dim3(grid_for(total)), dim3(kThreads), 0, s, c->pool, dst, ids_dev,
+                     total, make_div(c->block_bytes / 16), c->block_bytes);
+  return hipGetLastError();
+}
+
+hipError_t launch_scatter_blocks(const lkv_ctx *c, const int32_t *ids_dev, int64_t n, const char *src, hipStream_t s) {
+  int64_t total = n * (c->block_bytes / 16);
+  if (total == 0) return hipSuccess;
+  hipLaunchKernelGGL(move_blocks_kernel<false>, dim3(grid_for(total)), dim3(kThreads), 0, s, c->pool,
+                     const_cast<char *>(src), ids_dev, total, make_div(c->block_bytes / 16), c->block_bytes);
+  return hipGetLastError();
+}
+
+}  // namespace lkv

@@ -1,0 +1,488 @@
+// Host side of liblkv: context life cycle, the layer-wise block allocator and block tables
+// (paper Sections 3.2.1 and 3.2.2), and the stream/event orchestration of offload and reload
+// (Section 4).  All arithmetic on KV data happens in the kernels; this file only validates,
+// keeps the logical state and enqueues.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "lkv_internal.hpp"
+
+namespace {
+
+thread_local std::string g_create_error;
+
+lkv_status fail(const lkv_ctx *c, lkv_status st, const char *fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (c) c->err = buf; else g_create_error = buf;
+  return st;
+}
+
+#define LKV_HIP(c, call)                                                                   \
+  do {                                                                                     \
+    hipError_t e_ = (call);                                                                \
+    if (e_ != hipSuccess)                                                                  \
+      return fail((c), LKV_ERR_DEVICE, "%s failed: %s", #call, hipGetErrorString(e_));      \
+  } while (0)
+
+hipEvent_t &event_of(lkv_ctx *c, int32_t layer, int32_t ev) { return c->events[(size_t)layer * 4 + ev]; }
+
+lkv_status record_event(lkv_ctx *c, int32_t layer, int32_t ev, hipStream_t s) {
+  LKV_HIP(c, hipEventRecord(event_of(c, layer, ev), s));
+  c->event_recorded[(size_t)layer * 4 + ev] = 1;
+  return LKV_OK;
+}
+
+lkv_status wait_event(lkv_ctx *c, int32_t layer, int32_t ev, hipStream_t s) {
+  if (c->event_recorded[(size_t)layer * 4 + ev])
+    LKV_HIP(c, hipStreamWaitEvent(s, event_of(c, layer, ev), 0));
+  return LKV_OK;
+}
+
+bool bad_layer(const lkv_ctx *c, int32_t layer) { return layer < 0 || layer >= c->cfg.num_layers; }
+
+lkv_status staging_create(lkv_ctx *c, lkv::Staging &st) {
+  LKV_HIP(c, hipMalloc((void **)&st.buf, (size_t)(c->staging_blocks * c->block_bytes)));
+  size_t ids_bytes = sizeof(int32_t) * (size_t)c->staging_blocks * lkv::Staging::kSlots;
+  LKV_HIP(c, hipMalloc((void **)&st.ids_dev, ids_bytes));
+  LKV_HIP(c, hipHostMalloc((void **)&st.ids_pinned, ids_bytes, hipHostMallocDefault));
+  for (auto &e : st.slot_done) LKV_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+  LKV_HIP(c, hipEventCreateWithFlags(&st.buf_free, hipEventDisableTiming));
+  return LKV_OK;
+}
+
+void staging_destroy(lkv::Staging &st) {
+  if (st.buf) (void)hipFree(st.buf);
+  if (st.ids_dev) (void)hipFree(st.ids_dev);
+  if (st.ids_pinned) (void)hipHostFree(st.ids_pinned);
+  for (auto &e : st.slot_done)
+    if (e) (void)hipEventDestroy(e);
+  if (st.buf_free) (void)hipEventDestroy(st.buf_free);
+  st = lkv::Staging{};
+}
+
+// Puts ids[0..n) into the next slot of the ring and enqueues their copy to the device.
+lkv_status stage_ids(lkv_ctx *c, lkv::Staging &st, const int32_t *ids, int64_t n, hipStream_t s,
+                     int *slot_out) {
+  int slot = st.next_slot;
+  st.next_slot = (st.next_slot + 1) % lkv::Staging::kSlots;
+  // the slot's previous kernel must have consumed its ids before the host overwrites them
+  LKV_HIP(c, hipEventSynchronize(st.slot_done[slot]));
+  int32_t *pinned = st.ids_pinned + (size_t)slot * c->staging_blocks;
+  int32_t *dev = st.ids_dev + (size_t)slot * c->staging_blocks;
+  std::memcpy(pinned, ids, sizeof(int32_t) * (size_t)n);
+  LKV_HIP(c, hipMemcpyAsync(dev, pinned, sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice, s));
+  *slot_out = slot;
+  return LKV_OK;
+}
+
+lkv_status check_ids(const lkv_ctx *c, const int32_t *ids, int64_t n) {
+  for (int64_t i = 0; i < n; ++i)
+    if (ids[i] < 0 || ids[i] >= c->cfg.num_pool_blocks)
+      return fail(c, LKV_ERR_INVALID_ARG, "block_ids[%lld] = %d is outside the pool (%lld blocks)",
+                  (long long)i, ids[i], (long long)c->cfg.num_pool_blocks);
+  return LKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+static lkv_status create_impl(const lkv_config *cfg, lkv_ctx **out, bool with_device) {
+  if (!cfg || !out) return fail(nullptr, LKV_ERR_INVALID_ARG, "lkv_create: NULL argument");
+  *out = nullptr;
+  if (cfg->num_layers <= 0 || cfg->num_q_heads <= 0 || cfg->num_kv_heads <= 0 || cfg->head_dim <= 0 ||
+      cfg->block_size <= 0 || cfg->num_pool_blocks <= 0)
+    return fail(nullptr, LKV_ERR_INVALID_ARG, "lkv_create: sizes must be positive");
+  if (cfg->num_q_heads % cfg->num_kv_heads)
+    return fail(nullptr, LKV_ERR_INVALID_ARG, "lkv_create: num_kv_heads must divide num_q_heads");
+  if (cfg->dtype != LKV_F32 && cfg->dtype != LKV_BF16)
+    return fail(nullptr, LKV_ERR_INVALID_ARG, "lkv_create: unknown dtype %d", cfg->dtype);
+  if (cfg->num_pool_blocks > INT32_MAX)
+    return fail(nullptr, LKV_ERR_INVALID_ARG, "lkv_create: block ids are 32-bit");
+  if (cfg->decode_partition < 0 || cfg->decode_partition % 64)
+    return fail(nullptr, LKV_ERR_INVALID_ARG, "lkv_create: decode_partition must be a multiple of 64");
+  int64_t elem = cfg->dtype == LKV_F32 ? 4 : 2;
+  if ((cfg->head_dim * elem) % 16)
+    return fail(nullptr, LKV_ERR_UNSUPPORTED, "lkv_create: head_dim*element size must be a multiple of 16 bytes");
+  if (cfg->pool && ((uintptr_t)cfg->pool & 255))
+    return fail(nullptr, LKV_ERR_INVALID_ARG, "lkv_create: pool must be 256-byte aligned");
+
+  lkv_ctx *c = new (std::nothrow) lkv_ctx();
+  if (!c) return fail(nullptr, LKV_ERR_HOST_MEMORY, "lkv_create: out of host memory");
+  c->cfg = *cfg;
+  c->elem = elem;
+  c->row_bytes = cfg->head_dim * elem;
+  c->token_bytes = 2 * cfg->num_kv_heads * c->row_bytes;
+  c->block_bytes = cfg->block_size * c->token_bytes;
+  c->scale = cfg->softmax_scale != 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
+  int64_t staging = cfg->staging_bytes > 0 ? cfg->staging_bytes : (int64_t)256 << 20;
+  c->staging_blocks = staging / c->block_bytes;
+  if (c->staging_blocks < 1) c->staging_blocks = 1;
+  if (c->staging_blocks > cfg->num_pool_blocks) c->staging_blocks = cfg->num_pool_blocks;
+
+  auto bail = [&](lkv_status st) {
+    g_create_error = c->err;
+    lkv_destroy(c);
+    return st;
+  };
+  c->free_list.resize((size_t)cfg->num_pool_blocks);
+  for (int64_t i = 0; i < cfg->num_pool_blocks; ++i)
+    c->free_list[(size_t)i] = (int32_t)(cfg->num_pool_blocks - 1 - i);  // id 0 handed out first
+  if (!with_device) {
+    c->logical_only = true;
+    *out = c;
+    return LKV_OK;
+  }
+  hipError_t e = hipGetDevice(&c->device);
+  if (e != hipSuccess) {
+    c->err = std::string("hipGetDevice failed: ") + hipGetErrorString(e);
+    return bail(LKV_ERR_DEVICE);
+  }
+  if (cfg->pool) {
+    c->pool = (char *)cfg->pool;
+  } else {
+    e = hipMalloc((void **)&c->pool, (size_t)(cfg->num_pool_blocks * c->block_bytes));
+    if (e != hipSuccess) {
+      c->pool = nullptr;
+      c->err = std::string("hipMalloc of the pool failed: ") + hipGetErrorString(e);
+      return bail(LKV_ERR_DEVICE);
+    }
+    c->owns_pool = true;
+  }
+  lkv_status st = staging_create(c, c->d2h);
+  if (st == LKV_OK) st = staging_create(c, c->h2d);
+  if (st != LKV_OK) return bail(st);
+  c->events.assign((size_t)cfg->num_layers * 4, nullptr);
+  c->event_recorded.assign((size_t)cfg->num_layers * 4, 0);
+  for (auto &ev : c->events) {
+    e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+    if (e != hipSuccess) {
+      c->err = std::string("hipEventCreate failed: ") + hipGetErrorString(e);
+      return bail(LKV_ERR_DEVICE);
+    }
+  }
+  *out = c;
+  return LKV_OK;
+}
+
+lkv_status lkv_create(const lkv_config *cfg, lkv_ctx **out) { return create_impl(cfg, out, true); }
+lkv_status lkv_create_logical(const lkv_config *cfg, lkv_ctx **out) { return create_impl(cfg, out, false); }
+
+void lkv_destroy(lkv_ctx *c) {
+  if (!c) return;
+  if (c->logical_only) {
+    delete c;
+    return;
+  }
+  (void)hipDeviceSynchronize();
+  staging_destroy(c->d2h);
+  staging_destroy(c->h2d);
+  for (auto &ev : c->events)
+    if (ev) (void)hipEventDestroy(ev);
+  if (c->ws) (void)hipFree(c->ws);
+  if (c->owns_pool && c->pool) (void)hipFree(c->pool);
+  delete c;
+}
+
+const char *lkv_last_error(const lkv_ctx *c) { return c ? c->err.c_str() : g_create_error.c_str(); }
+
+lkv_status lkv_pool_info(const lkv_ctx *c, void **pool, int64_t *bytes, int64_t *block_bytes) {
+  if (!c) return LKV_ERR_INVALID_ARG;
+  if (pool) *pool = c->pool;
+  if (bytes) *bytes = c->cfg.num_pool_blocks * c->block_bytes;
+  if (block_bytes) *block_bytes = c->block_bytes;
+  return LKV_OK;
+}
+
+// ---------------------------------------------------------------- logical state
+lkv_status lkv_pool_reset(lkv_ctx *c, const int32_t *free_order, int64_t n) {
+  if (!c) return LKV_ERR_INVALID_ARG;
+  if (!free_order || n != c->cfg.num_pool_blocks)
+    return fail(c, LKV_ERR_INVALID_ARG, "lkv_pool_reset: free_order must list all %lld blocks",
+                (long long)c->cfg.num_pool_blocks);
+  std::vector<uint8_t> seen((size_t)n, 0);
+  for (int64_t i = 0; i < n; ++i) {
+    int32_t b = free_order[i];
+    if (b < 0 || b >= n || seen[(size_t)b])
+      return fail(c, LKV_ERR_INVALID_ARG, "lkv_pool_reset: free_order is not a permutation (entry %lld)", (long long)i);
+    seen[(size_t)b] = 1;
+  }
+  c->layers.clear();
+  c->free_list.resize((size_t)n);
+  for (int64_t i = 0; i < n; ++i) c->free_list[(size_t)(n - 1 - i)] = free_order[i];
+  return LKV_OK;
+}
+
+lkv_status lkv_alloc_layer_blocks(lkv_ctx *c, int64_t seq, int32_t layer, int64_t num_tokens_total) {
+  if (!c) return LKV_ERR_INVALID_ARG;
+  if (bad_layer(c, layer) || num_tokens_total < 0)
+    return fail(c, LKV_ERR_INVALID_ARG, "lkv_alloc_layer_blocks: bad layer %d or token count %lld", layer,
+                (long long)num_tokens_total);
+  int64_t bs = c->cfg.block_size;
+  int64_t want = (num_tokens_total + bs - 1) / bs;
+  auto it = c->layers.find({seq, layer});
+  int64_t have = it == c->layers.end() ? 0 : (int64_t)it->second.table.size();
+  int64_t grow = want > have ? want - have : 0;
+  if (grow > (int64_t)c->free_list.size())
+    return fail(c, LKV_ERR_NO_BLOCKS, "lkv_alloc_layer_blocks: need %lld blocks, %lld free", (long long)grow,
+                (long long)c->free_list.size());
+  lkv::LayerState &st = c->layers[{seq, layer}];
+  st.table.reserve((size_t)(have + grow));
+  for (int64_t i = 0; i < grow; ++i) {
+    st.table.push_back(c->free_list.back());
+    c->free_list.pop_back();
+  }
+  st.residency = LKV_RES_GPU;
+  return LKV_OK;
+}
+
+lkv_status lkv_free_layer_blocks(lkv_ctx *c, int64_t seq, int32_t layer, int32_t to_host) {
+  if (!c) return LKV_ERR_INVALID_ARG;
+  if (bad_layer(c, layer)) return fail(c, LKV_ERR_INVALID_ARG, "lkv_free_layer_blocks: bad layer %d", layer);
+  auto it = c->layers.find({seq, layer});
+  if (it == c->layers.end() || it->second.residency != LKV_RES_GPU)
+    return fail(c, LKV_ERR_NOT_RESIDENT, "lkv_free_layer_blocks: (seq %lld, layer %d) holds no blocks",
+                (long long)seq, layer);
+  for (int32_t b : it->second.table) c->free_list.push_back(b);
+  if (to_host) {
+    it->second.table.clear();
+    it->second.residency = LKV_RES_HOST;
+  } else {
+    c->layers.erase(it);
+  }
+  return LKV_OK;
+}
+
+lkv_status lkv_free_seq(lkv_ctx *c, int64_t seq) {
+  if (!c) return LKV_ERR_INVALID_ARG;
+  for (int32_t layer = 0; layer < c->cfg.num_layers; ++layer) {
+    auto it = c->layers.find({seq, layer});
+    if (it == c->layers.end()) continue;
+    for (int32_t b : it->second.table) c->free_list.push_back(b);
+    c->layers.erase(it);
+  }
+  return LKV_OK;
+}
+
+lkv_status lkv_get_block_table(const lkv_ctx *c, int64_t seq, int32_t layer, int32_t *out, int64_t cap, int64_t *n) {
+  if (!c) return LKV_ERR_INVALID_ARG;
+  if (bad_layer(c, layer) || !n || cap < 0) return fail(c, LKV_ERR_INVALID_ARG, "lkv_get_block_table: bad argument");
+  auto it = c->layers.find({seq, layer});
+  if (it == c->layers.end()) {
+    *n = 0;
+    return LKV_OK;
+  }
+  if (it->second.residency == LKV_RES_HOST) {
+    *n = 0;
+    return fail(c, LKV_ERR_NOT_RESIDENT, "lkv_get_block_table: (seq %lld, layer %d) is on the host", (long long)seq, layer);
+  }
+  *n = (int64_t)it->second.table.size();
+  if (*n > cap || (*n && !out))
+    return fail(c, LKV_ERR_INVALID_ARG, "lkv_get_block_table: table has %lld entries, capacity %lld", (long long)*n,
+                (long long)cap);
+  if (*n) std::memcpy(out, it->second.table.data(), sizeof(int32_t) * (size_t)*n);
+  return LKV_OK;
+}
+
+lkv_status lkv_build_slot_mapping(const lkv_ctx *c, int64_t seq, int32_t layer, int64_t pos0, int64_t count,
+                                  int64_t *out) {
+  if (!c) return LKV_ERR_INVALID_ARG;
+  if (bad_layer(c, layer) || pos0 < 0 || count < 0 || (count && !out))
+    return fail(c, LKV_ERR_INVALID_ARG, "lkv_build_slot_mapping: bad argument");
+  auto it = c->layers.find({seq, layer});
+  if (it == c->layers.end() || it->second.residency != LKV_RES_GPU)
+    return fail(c, LKV_ERR_NOT_RESIDENT, "lkv_build_slot_mapping: (seq %lld, layer %d) is not in the pool",
+                (long long)seq, layer);
+  const auto &t = it->second.table;
+  int64_t bs = c->cfg.block_size;
+  if ((pos0 + count + bs - 1) / bs > (int64_t)t.size())
+    return fail(c, LKV_ERR_INVALID_ARG, "lkv_build_slot_mapping: positions %lld..%lld exceed the %zu allocated blocks",
+                (long long)pos0, (long long)(pos0 + count), t.size());
+  for (int64_t i = 0; i < count; ++i) {
+    int64_t p = pos0 + i;
+    out[i] = (int64_t)t[(size_t)(p / bs)] * bs + p % bs;
+  }
+  return LKV_OK;
+}
+
+lkv_status lkv_layer_residency(const lkv_ctx *c, int64_t seq, int32_t layer, int32_t *out) {
+  if (!c) return LKV_ERR_INVALID_ARG;
+  if (bad_layer(c, layer) || !out) return fail(c, LKV_ERR_INVALID_ARG, "lkv_layer_residency: bad argument");
+  auto it = c->layers.find({seq, layer});
+  *out = it == c->layers.end() ? (int32_t)LKV_RES_NONE : it->second.residency;
+  return LKV_OK;
+}
+
+int64_t lkv_num_free_blocks(const lkv_ctx *c) { return c ? (int64_t)c->free_list.size() : -1; }
+
+lkv_status lkv_plan_retained_layers(int32_t num_layers, int32_t x, int32_t *mask) {
+  if (num_layers <= 0 || x < 0 || x > num_layers || !mask) return LKV_ERR_INVALID_ARG;
+  // The retained share after l layers is the integer part of l*x/L; a layer is retained when
+  // taking it raises that share, which spaces the retained layers evenly.
+  int64_t before = 0;
+  for (int32_t l = 0; l < num_layers; ++l) {
+    int64_t after = ((int64_t)(l + 1) * x) / num_layers;
+    mask[l] = after > before ? 1 : 0;
+    before = after;
+  }
+  return LKV_OK;
+}
+
+// ---------------------------------------------------------------- device hot path
+lkv_status lkv_write_kv(lkv_ctx *c, int32_t layer, const void *K, const void *V, const int64_t *slot_mapping,
+                        int64_t num_tokens, void *stream) {
+  if (!c) return LKV_ERR_INVALID_ARG;
+  if (c->logical_only) return fail(c, LKV_ERR_DEVICE, "lkv_write_kv: this context has no device resources (lkv_create_logical)");
+  if (bad_layer(c, layer) || num_tokens < 0) return fail(c, LKV_ERR_INVALID_ARG, "lkv_write_kv: bad layer or count");
+  hipStream_t s = (hipStream_t)stream;
+  // a reload of this layer that is still in flight rewrites whole blocks: stay behind it
+  if (lkv_status st = wait_event(c, layer, LKV_EV_RELOADED, s)) return st;
+  if (num_tokens > 0) {
+    if (!K || !V || !slot_mapping) return fail(c, LKV_ERR_INVALID_ARG, "lkv_write_kv: NULL pointer");
+    if (((uintptr_t)K | (uintptr_t)V) & 15) return fail(c, LKV_ERR_INVALID_ARG, "lkv_write_kv: K and V must be 16-byte aligned");
+    LKV_HIP(c, lkv::launch_write_kv(c, K, V, slot_mapping, num_tokens, s));
+  }
+  c->stats.write_kv_calls += 1;
+  c->stats.write_kv_bytes += num_tokens * c->token_bytes;
+  return record_event(c, layer, LKV_EV_KV_WRITTEN, s);
+}
+
+lkv_status lkv_prefill_attention(lkv_ctx *c, int32_t layer, const void *Q, const void *K, const void *V, void *O,
+                                 const int32_t *cu_seqlens, int32_t num_seqs, int32_t max_seqlen,
+                                 int64_t total_tokens, int32_t causal, void *stream) {
+  if (!c) return LKV_ERR_INVALID_ARG;
+  if (c->logical_only) return fail(c, LKV_ERR_DEVICE, "lkv_prefill_attention: this context has no device resources (lkv_create_logical)");
+  if (bad_layer(c, layer) || num_seqs < 0 || max_seqlen < 0 || total_tokens < 0)
+    return fail(c, LKV_ERR_INVALID_ARG, "lkv_prefill_attention: bad layer or count");
+  if (!lkv::prefill_supported(c))
+    return fail(c, LKV_ERR_UNSUPPORTED, "lkv_prefill_attention: head_dim %d with dtype %d is not built", c->cfg.head_dim,
+                c->cfg.dtype);
+  if (num_seqs == 0 || max_seqlen == 0 || total_tokens == 0) return LKV_OK;
+  if (!Q || !K || !V || !O || !cu_seqlens) return fail(c, LKV_ERR_INVALID_ARG, "lkv_prefill_attention: NULL pointer");
+  if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15)
+    return fail(c, LKV_ERR_INVALID_ARG, "lkv_prefill_attention: tensors must be 16-byte aligned");
+  LKV_HIP(c, lkv::launch_prefill(c, Q, K, V, O, cu_seqlens, num_seqs, max_seqlen, causal, (hipStream_t)stream));
+  c->stats.prefill_calls += 1;
+  return LKV_OK;
+}
+
+lkv_status lkv_pack_layer_blocks(lkv_ctx *c, int32_t layer, const int32_t *block_ids, int64_t n, void *pinned_dst,
+                                 void *stream) {
+  if (!c) return LKV_ERR_INVALID_ARG;
+  if (c->logical_only) return fail(c, LKV_ERR_DEVICE, "lkv_pack_layer_blocks: this context has no device resources (lkv_create_logical)");
+  if (bad_layer(c, layer) || n < 0 || (n && (!block_ids || !pinned_dst)))
+    return fail(c, LKV_ERR_INVALID_ARG, "lkv_pack_layer_blocks: bad argument");
+  if (lkv_status st = check_ids(c, block_ids, n)) return st;
+  hipStream_t s = (hipStream_t)stream;
+  if (lkv_status st = wait_event(c, layer, LKV_EV_KV_WRITTEN, s)) return st;
+  lkv::Staging &sg = c->d2h;
+  for (int64_t first = 0; first < n; first += c->staging_blocks) {
+    int64_t m = n - first < c->staging_blocks ? n - first : c->staging_blocks;
+    int slot;
+    if (lkv_status st = stage_ids(c, sg, block_ids + first, m, s, &slot)) return st;
+    if (sg.buf_used) LKV_HIP(c, hipStreamWaitEvent(s, sg.buf_free, 0));
+    LKV_HIP(c, lkv::launch_gather_blocks(c, sg.ids_dev + (size_t)slot * c->staging_blocks, m, sg.buf, s));
+    LKV_HIP(c, hipEventRecord(sg.slot_done[slot], s));
+    if (first + m == n)
+      if (lkv_status st = record_event(c, layer, LKV_EV_PACKED, s)) return st;
+    LKV_HIP(c, hipMemcpyAsync((char *)pinned_dst + first * c->block_bytes, sg.buf, (size_t)(m * c->block_bytes),
+                              hipMemcpyDeviceToHost, s));
+    LKV_HIP(c, hipEventRecord(sg.buf_free, s));
+    sg.buf_used = true;
+  }
+  if (n == 0)
+    if (lkv_status st = record_event(c, layer, LKV_EV_PACKED, s)) return st;
+  c->stats.pack_calls += 1;
+  c->stats.pack_bytes += n * c->block_bytes;
+  return record_event(c, layer, LKV_EV_OFFLOADED, s);
+}
+
+lkv_status lkv_unpack_layer_blocks(lkv_ctx *c, int32_t layer, const int32_t *block_ids, int64_t n,
+                                   const void *pinned_src, void *stream) {
+  if (!c) return LKV_ERR_INVALID_ARG;
+  if (c->logical_only) return fail(c, LKV_ERR_DEVICE, "lkv_unpack_layer_blocks: this context has no device resources (lkv_create_logical)");
+  if (bad_layer(c, layer) || n < 0 || (n && (!block_ids || !pinned_src)))
+    return fail(c, LKV_ERR_INVALID_ARG, "lkv_unpack_layer_blocks: bad argument");
+  if (lkv_status st = check_ids(c, block_ids, n)) return st;
+  hipStream_t s = (hipStream_t)stream;
+  lkv::Staging &sg = c->h2d;
+  for (int64_t first = 0; first < n; first += c->staging_blocks) {
+    int64_t m = n - first < c->staging_blocks ? n - first : c->staging_blocks;
+    int slot;
+    if (lkv_status st = stage_ids(c, sg, block_ids + first, m, s, &slot)) return st;
+    if (sg.buf_used) LKV_HIP(c, hipStreamWaitEvent(s, sg.buf_free, 0));
+    LKV_HIP(c, hipMemcpyAsync(sg.buf, (const char *)pinned_src + first * c->block_bytes, (size_t)(m * c->block_bytes),
+                              hipMemcpyHostToDevice, s));
+    LKV_HIP(c, lkv::launch_scatter_blocks(c, sg.ids_dev + (size_t)slot * c->staging_blocks, m, sg.buf, s));
+    LKV_HIP(c, hipEventRecord(sg.slot_done[slot], s));
+    LKV_HIP(c, hipEventRecord(sg.buf_free, s));
+    sg.buf_used = true;
+  }
+  c->stats.unpack_calls += 1;
+  c->stats.unpack_bytes += n * c->block_bytes;
+  return record_event(c, layer, LKV_EV_RELOADED, s);
+}
+
+lkv_status lkv_paged_decode_attention(lkv_ctx *c, int32_t layer, const void *Q, void *O, const int32_t *block_table,
+                                      int32_t max_blocks_per_seq, const int32_t *context_lens, int32_t num_seqs,
+                                      void *stream) {
+  if (!c) return LKV_ERR_INVALID_ARG;
+  if (c->logical_only) return fail(c, LKV_ERR_DEVICE, "lkv_paged_decode_attention: this context has no device resources (lkv_create_logical)");
+  if (bad_layer(c, layer) || num_seqs < 0 || max_blocks_per_seq < 0)
+    return fail(c, LKV_ERR_INVALID_ARG, "lkv_paged_decode_attention: bad layer or count");
+  if (!lkv::decode_supported(c))
+    return fail(c, LKV_ERR_UNSUPPORTED, "lkv_paged_decode_attention: head_dim %d / block_size %d / dtype %d is not built",
+                c->cfg.head_dim, c->cfg.block_size, c->cfg.dtype);
+  if (num_seqs == 0) return LKV_OK;
+  if (!Q || !O || !context_lens || (max_blocks_per_seq && !block_table))
+    return fail(c, LKV_ERR_INVALID_ARG, "lkv_paged_decode_attention: NULL pointer");
+  if (((uintptr_t)Q | (uintptr_t)O) & 15)
+    return fail(c, LKV_ERR_INVALID_ARG, "lkv_paged_decode_attention: Q and O must be 16-byte aligned");
+  hipStream_t s = (hipStream_t)stream;
+  if (lkv_status st = wait_event(c, layer, LKV_EV_RELOADED, s)) return st;
+  int64_t need = lkv::decode_workspace_bytes(c, num_seqs, max_blocks_per_seq);
+  if (need > c->ws_bytes) {
+    // Earlier launches may still read the old workspace: drain before replacing it.
+    LKV_HIP(c, hipDeviceSynchronize());
+    if (c->ws) LKV_HIP(c, hipFree(c->ws));
+    c->ws = nullptr;
+    c->ws_bytes = 0;
+    LKV_HIP(c, hipMalloc((void **)&c->ws, (size_t)need));
+    c->ws_bytes = need;
+  }
+  LKV_HIP(c, lkv::launch_paged_decode(c, Q, O, block_table, max_blocks_per_seq, context_lens, num_seqs, c->ws, s));
+  c->stats.decode_calls += 1;
+  return LKV_OK;
+}
+
+// ---------------------------------------------------------------- ordering and statistics
+lkv_status lkv_stream_wait_event(lkv_ctx *c, int32_t layer, int32_t ev, void *stream) {
+  if (!c) return LKV_ERR_INVALID_ARG;
+  if (c->logical_only) return fail(c, LKV_ERR_DEVICE, "lkv_stream_wait_event: this context has no device resources (lkv_create_logical)");
+  if (bad_layer(c, layer) || ev < 0 || ev > 3) return fail(c, LKV_ERR_INVALID_ARG, "lkv_stream_wait_event: bad argument");
+  return wait_event(c, layer, ev, (hipStream_t)stream);
+}
+
+lkv_status lkv_event_synchronize(lkv_ctx *c, int32_t layer, int32_t ev) {
+  if (!c) return LKV_ERR_INVALID_ARG;
+  if (c->logical_only) return fail(c, LKV_ERR_DEVICE, "lkv_event_synchronize: this context has no device resources (lkv_create_logical)");
+  if (bad_layer(c, layer) || ev < 0 || ev > 3) return fail(c, LKV_ERR_INVALID_ARG, "lkv_event_synchronize: bad argument");
+  if (c->event_recorded[(size_t)layer * 4 + ev]) LKV_HIP(c, hipEventSynchronize(event_of(c, layer, ev)));
+  return LKV_OK;
+}
+
+lkv_status lkv_get_stats(const lkv_ctx *c, lkv_stats *out, int64_t size) {
+  if (!c || !out || size < 0) return LKV_ERR_INVALID_ARG;
+  size_t n = (size_t)size < sizeof(lkv_stats) ? (size_t)size : sizeof(lkv_stats);
+  std::memcpy(out, &c->stats, n);
+  return LKV_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,90 @@
+// Internal declarations shared by the host code and the kernel launchers of liblkv.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "lkv.h"
+
+namespace lkv {
+
+struct LayerKey {
+  int64_t seq;
+  int32_t layer;
+  bool operator==(const LayerKey &o) const { return seq == o.seq && layer == o.layer; }
+};
+struct LayerKeyHash {
+  size_t operator()(const LayerKey &k) const {
+    return std::hash<int64_t>()(k.seq * 1000003 + k.layer);
+  }
+};
+struct LayerState {
+  std::vector<int32_t> table;  // block ids in token order
+  int32_t residency = LKV_RES_NONE;
+};
+
+// One transfer direction's device staging plus the bookkeeping that keeps two streams from
+// using it at once.
+struct Staging {
+  char *buf = nullptr;          // device
+  int32_t *ids_dev = nullptr;   // device, capacity ids_cap per slot
+  int32_t *ids_pinned = nullptr;  // pinned host mirror, same shape
+  static constexpr int kSlots = 8;
+  hipEvent_t slot_done[kSlots] = {};  // ids slot consumed by its kernel
+  int next_slot = 0;
+  hipEvent_t buf_free = nullptr;  // last user of buf has finished with it
+  bool buf_used = false;
+};
+
+}  // namespace lkv
+
+struct lkv_ctx {
+  lkv_config cfg{};
+  int device = 0;
+  int64_t elem = 0;         // bytes per element
+  int64_t row_bytes = 0;    // head_dim*elem
+  int64_t token_bytes = 0;  // tau
+  int64_t block_bytes = 0;  // beta
+  float scale = 0.f;
+  char *pool = nullptr;
+  bool owns_pool = false;
+  bool logical_only = false;  // created without device resources: host state only
+  int64_t staging_blocks = 0;  // blocks that fit one staging buffer
+  lkv::Staging d2h, h2d;
+  std::vector<hipEvent_t> events;  // [layer][4]
+  std::vector<uint8_t> event_recorded;
+  // split-K workspace of decode attention
+  float *ws = nullptr;
+  int64_t ws_bytes = 0;
+  // logical state
+  std::vector<int32_t> free_list;  // stack, back() is handed out next
+  std::unordered_map<lkv::LayerKey, lkv::LayerState, lkv::LayerKeyHash> layers;
+  lkv_stats stats{};
+  mutable std::string err;
+};
+
+namespace lkv {
+
+// All launchers return hipSuccess or the launch error; arguments are validated by the callers.
+hipError_t launch_write_kv(const lkv_ctx *c, const void *K, const void *V, const int64_t *slots,
+                           int64_t num_tokens, hipStream_t s);
+// gather: dst[i*beta ..] = pool[ids[i]*beta ..];  scatter: the inverse.
+hipError_t launch_gather_blocks(const lkv_ctx *c, const int32_t *ids_dev, int64_t n, char *dst, hipStream_t s);
+hipError_t launch_scatter_blocks(const lkv_ctx *c, const int32_t *ids_dev, int64_t n, const char *src, hipStream_t s);
+
+int64_t decode_workspace_bytes(const lkv_ctx *c, int32_t num_seqs, int32_t max_blocks_per_seq);
+hipError_t launch_paged_decode(const lkv_ctx *c, const void *Q, void *O, const int32_t *block_table,
+                               int32_t max_blocks_per_seq, const int32_t *context_lens, int32_t num_seqs,
+                               float *ws, hipStream_t s);
+bool decode_supported(const lkv_ctx *c);
+
+hipError_t launch_prefill(const lkv_ctx *c, const void *Q, const void *K, const void *V, void *O,
+                          const int32_t *cu_seqlens, int32_t num_seqs, int32_t max_seqlen, int32_t causal,
+                          hipStream_t s);
+bool prefill_supported(const lkv_ctx *c);
+
+}  // namespace lkv
