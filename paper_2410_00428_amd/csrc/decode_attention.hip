@@ -11,6 +11,9 @@
 // each group of lanes that shares a token sub-row keeps its own running (max, sum, output) and
 // the groups, then the wavefronts, then the partitions are merged with the usual
 // exp(m_i - m) weights.
+#include <cstdio>
+#include <cstdlib>
+
 #include "lkv_internal.hpp"
 
 namespace {
@@ -50,8 +53,28 @@ struct Workspace {
   float *o;   // [B][Hq][parts][D]
 };
 
-template <typename T, int D, int G>
-__global__ void __launch_bounds__(kThreads)
+// Sum over the LPR adjacent lanes that hold one row; every lane of the group gets the total.
+// Steps inside a 16-lane row are DPP adds (no LDS traffic); only a 32-lane row needs a shuffle.
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, false));
+}
+template <int LPR>
+__device__ __forceinline__ float row_sum(float x) {
+  if (LPR >= 2) x += dpp_mov<0xB1>(x);                       // quad_perm [1,0,3,2]
+  if (LPR >= 4) x += dpp_mov<0x4E>(x);                       // quad_perm [2,3,0,1]
+  if (LPR == 8) x += dpp_mov<0x141>(x);                      // row_half_mirror: the other quad of the 8
+  if (LPR >= 16) { x += dpp_mov<0x124>(x); x += dpp_mov<0x128>(x); }  // row_ror 4, row_ror 8
+  if (LPR >= 32) x += __shfl_xor(x, 16);
+  return x;
+}
+
+template <typename T> __device__ __forceinline__ float fexp(float x);
+template <> __device__ __forceinline__ float fexp<float>(float x) { return expf(x); }       // fp32 parity path
+template <> __device__ __forceinline__ float fexp<uint16_t>(float x) { return __expf(x); }
+
+template <typename T, int D, int G, int WAVES>
+__global__ void __launch_bounds__(WAVES * 64)
 paged_decode_kernel(const T *__restrict__ Q, T *__restrict__ O, const char *__restrict__ pool,
                     const int32_t *__restrict__ block_table, int max_blocks, const int32_t *__restrict__ context_lens,
                     int Hq, int64_t block_bytes, float scale, int partition, int num_parts, Workspace ws) {
@@ -60,8 +83,9 @@ paged_decode_kernel(const T *__restrict__ Q, T *__restrict__ O, const char *__re
   constexpr int TPI = 64 / LPR;             // tokens covered by one wavefront load
   constexpr int NI = kBlock / TPI;          // loads per lane per block, for K and again for V
   constexpr int64_t kRowBytes = (int64_t)D * sizeof(T);
+  constexpr bool kPrefetch = G <= 2;        // two blocks in flight per wavefront while registers allow
 
-  const int part = blockIdx.x, g = blockIdx.y, s = blockIdx.z;
+  const int g = blockIdx.x, s = blockIdx.y, part = blockIdx.z;  // partition index slowest: see make_plan
   const int n = context_lens[s];
   const int start = part * partition;
   if (start >= n && part != 0) return;
@@ -86,59 +110,88 @@ paged_decode_kernel(const T *__restrict__ Q, T *__restrict__ O, const char *__re
     for (int e = 0; e < EPL; ++e) acc[j][e] = 0.f;
   }
 
+  // This wavefront's blocks: first, first+WAVES, ...  Their table entries are fetched 64 at a time,
+  // one per lane, and broadcast from that register as the loop reaches them.
+  const int first = start / kBlock + wave, nb_end = (end + kBlock - 1) / kBlock;
+  const int iters = first < nb_end ? (nb_end - first + WAVES - 1) / WAVES : 0;
   const int32_t *table = block_table + (int64_t)s * max_blocks;
-  for (int b = start / kBlock + wave; b * kBlock < end; b += kWaves) {
-    const int blk = __builtin_amdgcn_readfirstlane(table[b]);
-    const char *base = pool + (int64_t)blk * block_bytes + (int64_t)g * (2 * kBlock * kRowBytes) +
-                       (int64_t)r * kRowBytes + c * 16;
-    u32x4 kw[NI], vw[NI];
-#pragma unroll
-    for (int i = 0; i < NI; ++i) kw[i] = *(const u32x4 *)(base + (int64_t)i * TPI * kRowBytes);
-#pragma unroll
-    for (int i = 0; i < NI; ++i) vw[i] = *(const u32x4 *)(base + kBlock * kRowBytes + (int64_t)i * TPI * kRowBytes);
+  const char *lane_base = pool + (int64_t)g * (2 * kBlock * kRowBytes) + (int64_t)r * kRowBytes + c * 16;
 
-    float sc[G][NI];
-    bool valid[NI];
+  for (int it0 = 0; it0 < iters; it0 += 64) {
+    const int cnt = min(64, iters - it0);
+    const int my_entry = lane < cnt ? table[first + (it0 + lane) * WAVES] : 0;
+
+    auto load = [&](int it, u32x4 *kw, u32x4 *vw) {
+      const int blk = __builtin_amdgcn_readlane(my_entry, it);
+      const char *base = lane_base + (int64_t)blk * block_bytes;
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      valid[i] = b * kBlock + i * TPI + r < end;
-      float k[EPL];
-      Elem<T>::unpack(kw[i], k);
+      for (int i = 0; i < NI; ++i) kw[i] = *(const u32x4 *)(base + (int64_t)i * TPI * kRowBytes);
 #pragma unroll
-      for (int j = 0; j < G; ++j) {
-        float d = 0.f;
+      for (int i = 0; i < NI; ++i) vw[i] = *(const u32x4 *)(base + kBlock * kRowBytes + (int64_t)i * TPI * kRowBytes);
+    };
+    auto compute = [&](int it, const u32x4 *kw, const u32x4 *vw) {
+      const int tok0 = (first + (it0 + it) * WAVES) * kBlock + r;
+      float sc[G][NI];
+      bool valid[NI];
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) d = fmaf(q[j][e], k[e], d);
+      for (int i = 0; i < NI; ++i) {
+        valid[i] = tok0 + i * TPI < end;
+        float k[EPL];
+        Elem<T>::unpack(kw[i], k);
 #pragma unroll
-        for (int off = 1; off < LPR; off <<= 1) d += __shfl_xor(d, off);
-        sc[j][i] = valid[i] ? d : -INFINITY;  // a masked slot may hold anything, NaN included
+        for (int j = 0; j < G; ++j) {
+          float d = 0.f;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) d = fmaf(q[j][e], k[e], d);
+          d = row_sum<LPR>(d);
+          sc[j][i] = valid[i] ? d : -INFINITY;  // a masked slot may hold anything, NaN included
+        }
       }
-    }
-#pragma unroll
-    for (int j = 0; j < G; ++j) {
-      float mn = m[j];
-#pragma unroll
-      for (int i = 0; i < NI; ++i) mn = fmaxf(mn, sc[j][i]);
-      const float ms = safe_max(mn);
-      const float alpha = __expf(m[j] - ms);
-      m[j] = mn;
-      l[j] *= alpha;
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) acc[j][e] *= alpha;
-#pragma unroll
-      for (int i = 0; i < NI; ++i) sc[j][i] = __expf(sc[j][i] - ms);
-    }
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      float v[EPL];
-      Elem<T>::unpack(vw[i], v);
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) v[e] = valid[i] ? v[e] : 0.f;
 #pragma unroll
       for (int j = 0; j < G; ++j) {
-        l[j] += sc[j][i];
+        float mn = m[j];
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[j][e] = fmaf(sc[j][i], v[e], acc[j][e]);
+        for (int i = 0; i < NI; ++i) mn = fmaxf(mn, sc[j][i]);
+        const float ms = safe_max(mn);
+        const float alpha = fexp<T>(m[j] - ms);
+        m[j] = mn;
+        l[j] *= alpha;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[j][e] *= alpha;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) sc[j][i] = fexp<T>(sc[j][i] - ms);
+      }
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        float v[EPL];
+        Elem<T>::unpack(vw[i], v);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) v[e] = valid[i] ? v[e] : 0.f;
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+          l[j] += sc[j][i];
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) acc[j][e] = fmaf(sc[j][i], v[e], acc[j][e]);
+        }
+      }
+    };
+
+    if (kPrefetch) {
+      u32x4 ka[NI], va[NI], kb[NI], vb[NI];
+      load(0, ka, va);
+      for (int it = 0; it < cnt; it += 2) {
+        if (it + 1 < cnt) load(it + 1, kb, vb);
+        compute(it, ka, va);
+        if (it + 1 < cnt) {
+          if (it + 2 < cnt) load(it + 2, ka, va);
+          compute(it + 1, kb, vb);
+        }
+      }
+    } else {
+      u32x4 ka[NI], va[NI];
+      for (int it = 0; it < cnt; ++it) {
+        load(it, ka, va);
+        compute(it, ka, va);
       }
     }
   }
@@ -150,7 +203,7 @@ paged_decode_kernel(const T *__restrict__ Q, T *__restrict__ O, const char *__re
     for (int j = 0; j < G; ++j) {
       const float mo = __shfl_xor(m[j], off), lo = __shfl_xor(l[j], off);
       const float mn = fmaxf(m[j], mo), ms = safe_max(mn);
-      const float a = __expf(m[j] - ms), bsc = __expf(mo - ms);
+      const float a = fexp<T>(m[j] - ms), bsc = fexp<T>(mo - ms);
       l[j] = l[j] * a + lo * bsc;
 #pragma unroll
       for (int e = 0; e < EPL; ++e) acc[j][e] = acc[j][e] * a + __shfl_xor(acc[j][e], off) * bsc;
@@ -159,8 +212,8 @@ paged_decode_kernel(const T *__restrict__ Q, T *__restrict__ O, const char *__re
   }
 
   // merge the wavefronts through LDS
-  __shared__ float sm_ml[kWaves][G][2];
-  __shared__ float sm_o[kWaves][G][D];
+  __shared__ float sm_ml[WAVES][G][2];
+  __shared__ float sm_o[WAVES][G][D];
   if (r == 0) {
 #pragma unroll
     for (int j = 0; j < G; ++j) {
@@ -173,22 +226,215 @@ paged_decode_kernel(const T *__restrict__ Q, T *__restrict__ O, const char *__re
     }
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
+  for (int idx = threadIdx.x; idx < G * D; idx += WAVES * 64) {
     const int j = idx / D, col = idx % D;
     float mn = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) mn = fmaxf(mn, sm_ml[w][j][0]);
+    for (int w = 0; w < WAVES; ++w) mn = fmaxf(mn, sm_ml[w][j][0]);
     const float ms = safe_max(mn);
     float lt = 0.f, ot = 0.f;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      const float a = __expf(sm_ml[w][j][0] - ms);
+    for (int w = 0; w < WAVES; ++w) {
+      const float a = fexp<T>(sm_ml[w][j][0] - ms);
       lt += sm_ml[w][j][1] * a;
       ot += sm_o[w][j][col] * a;
     }
     const int64_t row = (int64_t)s * Hq + g * G + j;
     if (num_parts == 1) {
       Elem<T>::store(O + row * D + col, lt > 0.f ? ot / lt : 0.f);
+    } else {
+      const int64_t p = row * num_parts + part;
+      ws.o[p * D + col] = ot;
+      if (col == 0) {
+        ws.ml[p * 2] = mn;
+        ws.ml[p * 2 + 1] = lt;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// bf16, head_dim 128, any group size up to 16: the same streaming scheme with both products on the
+// matrix cores (v_mfma_f32_16x16x32_bf16), so that grouped-query heads cost no extra vector work.
+// A wavefront takes a PAIR of blocks (32 keys) per step.  Lane l = (c = l%16, hq = l/16).
+//   S^T = K Q^T   A operand: lane (c, hq) holds 16 bytes of key row kappa(c), taken straight from the
+//                 pool; two MFMA chains X and Y cover the pair with kappa_X(c) = 8*(c/4) + c%4 and
+//                 kappa_Y = kappa_X + 4, so that afterwards lane (q = c, hq) holds the scores of keys
+//                 8*hq .. 8*hq+7 of the pair: exactly the B operand of the second product.
+//   O^T = V^T P^T A operand: lane (c, hq) loads the 16-byte piece c of value rows 8*hq .. 8*hq+7
+//                 (a 16-lane group reads whole 256-byte rows) and transposes the 8x8 bf16 patch in
+//                 registers with v_perm_b32; patch row i is the operand of MFMA i, whose 16 output
+//                 rows are the channels 8*c + i.  Lane (q, hq) ends up with channels 32*hq .. 32*hq+31.
+// Rows of masked keys are zeroed before the product (a masked slot may hold NaN).
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ unsigned pack_bf16(float a, float b) {
+  f32x2 f = {a, b};
+  bf16x2 v = __builtin_convertvector(f, bf16x2);  // round to nearest even
+  return __builtin_bit_cast(unsigned, v);
+}
+
+template <int G, int WAVES, bool PREFETCH>
+__global__ void __launch_bounds__(WAVES * 64)
+paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, const char *__restrict__ pool,
+                         const int32_t *__restrict__ block_table, int max_blocks,
+                         const int32_t *__restrict__ context_lens, int Hq, int64_t block_bytes, float scale,
+                         int partition, int num_parts, Workspace ws) {
+  constexpr int D = 128;
+  constexpr int kRow = D * 2;  // bytes per key/value row
+  const int g = blockIdx.x, s = blockIdx.y, part = blockIdx.z;  // partition index slowest: see make_plan
+  const int n = context_lens[s];
+  const int start = part * partition;
+  if (start >= n && part != 0) return;
+  const int end = min(n, start + partition);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = lane & 15, hq = lane >> 4;
+
+  bf16x8 qop[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    u32x4 w = {0, 0, 0, 0};
+    if (c < G) w = *(const u32x4 *)(Q + ((int64_t)s * Hq + g * G + c) * D + 32 * kk + 8 * hq);
+    qop[kk] = __builtin_bit_cast(bf16x8, w);
+  }
+  f32x4 oacc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) oacc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m = -INFINITY, l = 0.f;
+
+  const int nb_begin = start / kBlock, nb_end = (end + kBlock - 1) / kBlock;
+  const int npairs = (nb_end - nb_begin + 1) / 2;
+  const int my_pairs = wave < npairs ? (npairs - wave + WAVES - 1) / WAVES : 0;
+  const int32_t *table = block_table + (int64_t)s * max_blocks;
+  // byte offsets inside a (block, head) run for the two roles of this lane
+  const int k_off = (8 * ((c >> 2) & 1) + (c & 3)) * kRow + 16 * hq;   // key row kappa_X(c) % 16, piece hq
+  const int v_off = kBlock * kRow + 8 * (hq & 1) * kRow + 16 * c;       // value rows 8*(hq%2)..+7, piece c
+  const bool k_second = c >= 8, v_second = hq >= 2;                     // which block of the pair
+  const int64_t head_off = (int64_t)g * (2 * kBlock * kRow);
+
+  for (int p0 = 0; p0 < my_pairs; p0 += 32) {
+    const int cnt = min(32, my_pairs - p0);
+    // lane i keeps the table entry of block i%2 of this wavefront's (p0 + i/2)-th pair
+    const int bidx = nb_begin + 2 * (wave + (p0 + (lane >> 1)) * WAVES) + (lane & 1);
+    const int my_entry = (lane < 2 * cnt && bidx < nb_end) ? table[bidx] : -1;
+
+    auto load = [&](int it, u32x4 *kx, u32x4 *ky, u32x4 *vr) {
+      const int id0 = __builtin_amdgcn_readlane(my_entry, 2 * it);
+      int id1 = __builtin_amdgcn_readlane(my_entry, 2 * it + 1);
+      if (id1 < 0) id1 = id0;  // odd block count: the pair's second half is fully masked
+      const char *b0 = pool + (int64_t)id0 * block_bytes + head_off;
+      const char *b1 = pool + (int64_t)id1 * block_bytes + head_off;
+      const char *kb = (k_second ? b1 : b0) + k_off;
+      const char *vb = (v_second ? b1 : b0) + v_off;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) kx[kk] = *(const u32x4 *)(kb + 64 * kk);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) ky[kk] = *(const u32x4 *)(kb + 4 * kRow + 64 * kk);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) vr[j] = *(const u32x4 *)(vb + j * kRow);
+    };
+    auto compute = [&](int it, const u32x4 *kx, const u32x4 *ky, u32x4 *vr) {
+      const int key0 = (nb_begin + 2 * (wave + (p0 + it) * WAVES)) * kBlock + 8 * hq;  // this lane's 8 keys
+      f32x4 sx = {0.f, 0.f, 0.f, 0.f}, sy = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        sx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kx[kk]), qop[kk], sx, 0, 0, 0);
+        sy = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ky[kk]), qop[kk], sy, 0, 0, 0);
+      }
+      float t[8];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        t[v] = key0 + v < end ? sx[v] * scale : -INFINITY;
+        t[4 + v] = key0 + 4 + v < end ? sy[v] * scale : -INFINITY;
+      }
+      float mx = t[0];
+#pragma unroll
+      for (int e = 1; e < 8; ++e) mx = fmaxf(mx, t[e]);
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float mn = fmaxf(m, mx), ms = safe_max(mn);
+      const float alpha = __expf(m - ms);
+      m = mn;
+      float psum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        t[e] = __expf(t[e] - ms);
+        psum += t[e];
+      }
+      l = l * alpha + psum;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) oacc[i] *= alpha;
+      u32x4 pw = {pack_bf16(t[0], t[1]), pack_bf16(t[2], t[3]), pack_bf16(t[4], t[5]), pack_bf16(t[6], t[7])};
+      const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (key0 + j >= end) vr[j] = u32x4{0, 0, 0, 0};
+      // 8x8 transpose of 16-bit elements: channel pair i/2 of key rows 2w, 2w+1 -> word w of patch row i
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const unsigned sel = (i & 1) ? 0x07060302u : 0x05040100u;
+        u32x4 a;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) a[w] = __builtin_amdgcn_perm(vr[2 * w + 1][i >> 1], vr[2 * w][i >> 1], sel);
+        oacc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), pb, oacc[i], 0, 0, 0);
+      }
+    };
+
+    if (PREFETCH) {
+      u32x4 kxa[4], kya[4], va[8], kxb[4], kyb[4], vb[8];
+      load(0, kxa, kya, va);
+      for (int it = 0; it < cnt; it += 2) {
+        if (it + 1 < cnt) load(it + 1, kxb, kyb, vb);
+        compute(it, kxa, kya, va);
+        if (it + 1 < cnt) {
+          if (it + 2 < cnt) load(it + 2, kxa, kya, va);
+          compute(it + 1, kxb, kyb, vb);
+        }
+      }
+    } else {
+      u32x4 kxa[4], kya[4], va[8];
+      for (int it = 0; it < cnt; ++it) {
+        load(it, kxa, kya, va);
+        compute(it, kxa, kya, va);
+      }
+    }
+  }
+  l += __shfl_xor(l, 16);
+  l += __shfl_xor(l, 32);
+
+  // merge the wavefronts through LDS; lane (q, hq) owns channels 32*hq + 8*v + i of query q
+  __shared__ float sm_ml[WAVES][G][2];
+  __shared__ float sm_o[WAVES][G][D];
+  if (c < G) {
+    if (hq == 0) {
+      sm_ml[wave][c][0] = m;
+      sm_ml[wave][c][1] = l;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) sm_o[wave][c][32 * hq + 8 * v + i] = oacc[i][v];
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < G * D; idx += WAVES * 64) {
+    const int j = idx / D, col = idx % D;
+    float mn = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) mn = fmaxf(mn, sm_ml[w][j][0]);
+    const float ms = safe_max(mn);
+    float lt = 0.f, ot = 0.f;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) {
+      const float a = __expf(sm_ml[w][j][0] - ms);
+      lt += sm_ml[w][j][1] * a;
+      ot += sm_o[w][j][col] * a;
+    }
+    const int64_t row = (int64_t)s * Hq + g * G + j;
+    if (num_parts == 1) {
+      Elem<uint16_t>::store(O + row * D + col, lt > 0.f ? ot / lt : 0.f);
     } else {
       const int64_t p = row * num_parts + part;
       ws.o[p * D + col] = ot;
@@ -215,36 +461,98 @@ decode_combine_kernel(T *__restrict__ O, const int32_t *__restrict__ context_len
   float lt = 0.f, ot = 0.f;
   for (int p = 0; p < parts; ++p) {
     const int64_t i = row * num_parts + p;
-    const float a = __expf(ws.ml[i * 2] - ms);
+    const float a = fexp<T>(ws.ml[i * 2] - ms);
     lt += ws.ml[i * 2 + 1] * a;
     ot += ws.o[i * D + col] * a;
   }
   Elem<T>::store(O + row * D + col, lt > 0.f ? ot / lt : 0.f);
 }
 
-int pick_partition(const lkv_ctx *c, int num_seqs, int max_blocks) {
-  if (c->cfg.decode_partition > 0) return c->cfg.decode_partition;
+// Tunables of the split: tokens per partition and wavefronts per workgroup.  The host cannot see
+// the context lengths (they live in device memory), so it sizes the grid from the table width.
+// The partition index is the SLOWEST grid dimension: workgroups are dealt round-robin to the 8 XCDs,
+// and with the partition fastest a short last partition (e.g. 2049 = 2048 + 1 tokens) would put all
+// the heavy workgroups on half of the XCDs.
+struct Plan {
+  int partition, num_parts, waves;
+  bool mfma, prefetch;
+};
+
+Plan make_plan(const lkv_ctx *c, int num_seqs, int max_blocks) {
   const int64_t tokens = (int64_t)max_blocks * kBlock;
-  int p = 512;
-  while (p > 128 && (int64_t)num_seqs * c->cfg.num_kv_heads * ((tokens + p - 1) / p) < 2048) p >>= 1;
+  const int64_t units = (int64_t)num_seqs * c->cfg.num_kv_heads;
+  Plan p{0, 1, 4, false, true};
+  p.mfma = c->cfg.dtype == LKV_BF16 && c->cfg.head_dim == 128;
+  if (p.mfma) {
+    // measured on MI355X over the four decode workloads: 8 wavefronts per workgroup, two block pairs in
+    // flight per wavefront, partitions of 4096 tokens (contexts up to 4096 are not split at all)
+    p.waves = 8;
+    p.partition = 4096;
+  } else {
+    p.partition = 512;
+    while (p.partition > 128 && units * ((tokens + p.partition - 1) / p.partition) < 2048) p.partition >>= 1;
+  }
+  if (c->cfg.decode_partition > 0) p.partition = c->cfg.decode_partition;
+  if (const char *t = getenv("LKV_DECODE_TUNE")) {  // development aid: "partition,waves,mfma,prefetch"
+    int a = 0, b = 0, m = 0, pf = 1;
+    if (sscanf(t, "%d,%d,%d,%d", &a, &b, &m, &pf) >= 2 && a > 0 && a % 64 == 0 &&
+        (b == 1 || b == 2 || b == 4 || b == 8 || b == 16)) {
+      p.partition = a;
+      p.waves = b;
+      p.mfma = m != 0 && p.mfma;
+      p.prefetch = pf != 0;
+    }
+  }
+  if (p.mfma && p.waves > 8) p.waves = 8;
+  if (!p.mfma && p.waves < 4) p.waves = 4;
+  p.num_parts = (int)((tokens + p.partition - 1) / p.partition);
+  if (p.num_parts < 1) p.num_parts = 1;
   return p;
+}
+
+template <typename T, int D, int G, int WAVES>
+hipError_t launch_w(const lkv_ctx *c, const Plan &p, const void *Q, void *O, const int32_t *bt, int max_blocks,
+                    const int32_t *cl, int num_seqs, Workspace ws, hipStream_t s) {
+  hipLaunchKernelGGL((paged_decode_kernel<T, D, G, WAVES>), dim3(c->cfg.num_kv_heads, num_seqs, p.num_parts),
+                     dim3(WAVES * 64), 0, s, (const T *)Q, (T *)O, c->pool, bt, max_blocks, cl, c->cfg.num_q_heads,
+                     c->block_bytes, c->scale, p.partition, p.num_parts, ws);
+  return hipGetLastError();
+}
+
+template <int G, int WAVES>
+hipError_t launch_mfma(const lkv_ctx *c, const Plan &p, const void *Q, void *O, const int32_t *bt, int max_blocks,
+                       const int32_t *cl, int num_seqs, Workspace ws, hipStream_t s) {
+  dim3 grid(c->cfg.num_kv_heads, num_seqs, p.num_parts), block(WAVES * 64);
+  if (p.prefetch)
+    hipLaunchKernelGGL((paged_decode_mfma_kernel<G, WAVES, true>), grid, block, 0, s, (const uint16_t *)Q,
+                       (uint16_t *)O, c->pool, bt, max_blocks, cl, c->cfg.num_q_heads, c->block_bytes, c->scale,
+                       p.partition, p.num_parts, ws);
+  else
+    hipLaunchKernelGGL((paged_decode_mfma_kernel<G, WAVES, false>), grid, block, 0, s, (const uint16_t *)Q,
+                       (uint16_t *)O, c->pool, bt, max_blocks, cl, c->cfg.num_q_heads, c->block_bytes, c->scale,
+                       p.partition, p.num_parts, ws);
+  return hipGetLastError();
 }
 
 template <typename T, int D, int G>
 hipError_t launch_t(const lkv_ctx *c, const void *Q, void *O, const int32_t *bt, int max_blocks, const int32_t *cl,
                     int num_seqs, float *wsbuf, hipStream_t s) {
-  const int partition = pick_partition(c, num_seqs, max_blocks);
-  int num_parts = (int)(((int64_t)max_blocks * kBlock + partition - 1) / partition);
-  if (num_parts < 1) num_parts = 1;
+  const Plan p = make_plan(c, num_seqs, max_blocks);
+  if (num_seqs > 65535 || p.num_parts > 65535) return hipErrorInvalidValue;  // grid y and z limits
   const int Hq = c->cfg.num_q_heads;
-  Workspace ws{wsbuf, wsbuf + (int64_t)num_seqs * Hq * num_parts * 2};
-  hipLaunchKernelGGL((paged_decode_kernel<T, D, G>), dim3(num_parts, c->cfg.num_kv_heads, num_seqs), dim3(kThreads), 0,
-                     s, (const T *)Q, (T *)O, c->pool, bt, max_blocks, cl, Hq, c->block_bytes, c->scale, partition,
-                     num_parts, ws);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess || num_parts == 1) return e;
-  hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(num_seqs * Hq), dim3(D), 0, s, (T *)O, cl, Hq, partition,
-                     num_parts, ws);
+  Workspace ws{wsbuf, wsbuf + (int64_t)num_seqs * Hq * p.num_parts * 2};
+  hipError_t e;
+  if (p.mfma && sizeof(T) == 2 && D == 128) {  // make_plan sets mfma only for this case
+    if (p.waves == 1) e = launch_mfma<G, 1>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
+    else if (p.waves == 2) e = launch_mfma<G, 2>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
+    else if (p.waves == 4) e = launch_mfma<G, 4>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
+    else e = launch_mfma<G, 8>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
+  } else if (p.waves <= 4) e = launch_w<T, D, G, 4>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
+  else if (p.waves == 8) e = launch_w<T, D, G, 8>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
+  else e = launch_w<T, D, G, 16>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
+  if (e != hipSuccess || p.num_parts == 1) return e;
+  hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(num_seqs * Hq), dim3(D), 0, s, (T *)O, cl, Hq, p.partition,
+                     p.num_parts, ws);
   return hipGetLastError();
 }
 
@@ -271,8 +579,7 @@ bool decode_supported(const lkv_ctx *c) {
 }
 
 int64_t decode_workspace_bytes(const lkv_ctx *c, int32_t num_seqs, int32_t max_blocks) {
-  const int partition = pick_partition(c, num_seqs, max_blocks);
-  const int64_t parts = ((int64_t)max_blocks * kBlock + partition - 1) / partition;
+  const int64_t parts = make_plan(c, num_seqs, max_blocks).num_parts;
   if (parts <= 1) return 0;
   return (int64_t)num_seqs * c->cfg.num_q_heads * parts * (2 + c->cfg.head_dim) * (int64_t)sizeof(float);
 }
