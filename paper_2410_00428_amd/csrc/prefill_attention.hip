@@ -28,7 +28,6 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
-constexpr int BM = 128;  // queries per workgroup
 constexpr int BN = 64;   // keys per tile
 constexpr int kXcds = 8;
 constexpr float kLog2e = 1.4426950408889634f;
@@ -39,173 +38,253 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
   return __builtin_bit_cast(unsigned, v);
 }
 
-template <int D, bool CAUSAL>
-__global__ void __launch_bounds__(kThreads)
+// QB blocks of 32 queries per wavefront (each K / V^T operand read from LDS feeds QB MFMAs; QB = 1 keeps
+// the kernel within 256 registers so that two workgroups share a CU and hide each other's latencies).
+// LDS is double-buffered: the next tile's global loads are issued before the current tile's math and
+// parked in registers until it is done, so there is one barrier per tile.
+template <int D, bool CAUSAL, int QB>
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 prefill_bf16_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
-                    uint16_t *__restrict__ O, const int32_t *__restrict__ cu_seqlens, int Hq, int Hkv,
-                    int tiles_per_seq, int total_wgs, float scale_log2e) {
-  constexpr int KS_STRIDE = D + 8;   // bf16 elements per K row in LDS (padding spreads rows over banks)
-  constexpr int VT_STRIDE = BN + 4;  // bf16 elements per transposed-V row
-  constexpr int OS_STRIDE = D + 8;
-  constexpr int KK = D / 16;         // MFMA steps over the head dimension
-  constexpr int DB = D / 32;         // 32-row blocks of O^T
+                     uint16_t *__restrict__ O, const int32_t *__restrict__ cu_seqlens, int Hq, int Hkv,
+                     int tiles_per_seq, int total_wgs, float scale_log2e) {
+  constexpr int WQ = 32 * QB;        // queries per wavefront
+  constexpr int BMQ = 4 * WQ;        // queries per workgroup
+  constexpr int KS_STRIDE = D + 8, VT_STRIDE = BN + 4, OS_STRIDE = D + 8;
+  constexpr int KK = D / 16, DB = D / 32;
   constexpr int KS_BYTES = BN * KS_STRIDE * 2, VT_BYTES = D * VT_STRIDE * 2;
-  constexpr int OS_BYTES = 4 * 32 * OS_STRIDE * 2;
-  constexpr int SMEM = (KS_BYTES + VT_BYTES) > OS_BYTES ? (KS_BYTES + VT_BYTES) : OS_BYTES;
+  constexpr int BUF_BYTES = KS_BYTES + VT_BYTES;
+  constexpr int OS_BYTES = 4 * WQ * OS_STRIDE * 2;
+  constexpr int SMEM = 2 * BUF_BYTES > OS_BYTES ? 2 * BUF_BYTES : OS_BYTES;
+  constexpr int KPIECES = BN * (D / 8), VPATCHES = (BN / 4) * (D / 8);
+  constexpr int KP = (KPIECES + kThreads - 1) / kThreads;    // 16-byte K pieces per thread per tile
+  constexpr int VP = (VPATCHES + kThreads - 1) / kThreads;   // 4-key x 8-channel V patches per thread per tile
   __shared__ __attribute__((aligned(16))) char smem[SMEM];
-  char *Ks = smem, *Vt = smem + KS_BYTES;
 
-  // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of logical
-  // tiles so the q tiles of one (sequence, head) share that XCD's L2.
   const int per_xcd = (total_wgs + kXcds - 1) / kXcds;
   const int logical = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
   if (logical >= total_wgs) return;
-  const int qt = tiles_per_seq - 1 - logical % tiles_per_seq;  // heaviest (last) q tile first
+  const int qt = tiles_per_seq - 1 - logical % tiles_per_seq;
   const int rest = logical / tiles_per_seq;
   const int h = rest % Hq, s = rest / Hq;
   const int t0 = cu_seqlens[s], n = cu_seqlens[s + 1] - t0;
-  const int q0 = qt * BM;
+  const int q0 = qt * BMQ;
   if (q0 >= n) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, ql = lane & 31, hh = lane >> 5;
   const int g = h / (Hq / Hkv);
   const int64_t q_stride = (int64_t)Hq * D, kv_stride = (int64_t)Hkv * D;
-  const int wq0 = q0 + wave * 32;  // first query of this wavefront
-  const int my_q = wq0 + ql;
+  const int wq0 = q0 + wave * WQ;
 
-  bf16x8 qreg[KK];
+  bf16x8 qreg[QB][KK];
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) {
-    u32x4 w = {0, 0, 0, 0};
-    if (my_q < n) w = *(const u32x4 *)(Q + (t0 + my_q) * q_stride + (int64_t)h * D + 16 * kk + 8 * hh);
-    qreg[kk] = __builtin_bit_cast(bf16x8, w);
+  for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const int q = min(wq0 + 32 * qb + ql, n - 1);  // rows past the end compute on a copy and are not stored
+      const u32x4 w = *(const u32x4 *)(Q + (t0 + q) * q_stride + (int64_t)h * D + 16 * kk + 8 * hh);
+      qreg[qb][kk] = __builtin_bit_cast(bf16x8, w);
+    }
+  f32x16 oacc[QB][DB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) oacc[qb][db][v] = 0.f;
+  float m[QB], lsum[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    m[qb] = -INFINITY;
+    lsum[qb] = 0.f;
   }
-  f32x16 oacc[DB];
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) oacc[db][v] = 0.f;
-  float m = -INFINITY, lsum = 0.f;
 
-  const int kv_end = CAUSAL ? min(n, q0 + BM) : n;
+  const int kv_end = CAUSAL ? min(n, q0 + BMQ) : n;
   const int ntiles = (kv_end + BN - 1) / BN;
   const uint16_t *Kg = K + (int64_t)t0 * kv_stride + (int64_t)g * D;
   const uint16_t *Vg = V + (int64_t)t0 * kv_stride + (int64_t)g * D;
 
-  for (int j = 0; j < ntiles; ++j) {
-    const int k0 = j * BN;
-    __syncthreads();  // the previous tile's LDS reads are finished
-    // K tile, row-major: 16 lanes per 2*D-byte row
-    for (int p = tid; p < BN * (D / 8); p += kThreads) {
-      const int row = p / (D / 8), pc = p % (D / 8);
-      u32x4 w = {0, 0, 0, 0};
-      if (k0 + row < n) w = *(const u32x4 *)(Kg + (int64_t)(k0 + row) * kv_stride + pc * 8);
-      *(u32x4 *)(Ks + (row * KS_STRIDE + pc * 8) * 2) = w;
-    }
-    // V tile, transposed: a thread takes 4 keys x 8 channels and writes 8 channel rows of 4 keys
-    for (int p = tid; p < (BN / 4) * (D / 8); p += kThreads) {
-      const int kg = p / (D / 8), dg = p % (D / 8);
-      u32x4 r[4];
+  // Global loads of a tile go through buffer descriptors that end with the sequence's last row: the
+  // address is a scalar tile offset plus a per-lane byte offset that never changes (no address arithmetic
+  // in the loop), and rows past the end of the sequence read as zeros without any branch.
+  u32x4 kreg[KP], vreg[VP][4];
+  unsigned koff[KP], voff[VP][4];
+  const unsigned row_bytes = (unsigned)kv_stride * 2;
+  const unsigned extent = (unsigned)(n - 1) * row_bytes + D * 2;
+  const __amdgpu_buffer_rsrc_t krsrc = __builtin_amdgcn_make_buffer_rsrc((void *)Kg, 0, extent, 0x00020000);
+  const __amdgpu_buffer_rsrc_t vrsrc = __builtin_amdgcn_make_buffer_rsrc((void *)Vg, 0, extent, 0x00020000);
 #pragma unroll
-      for (int kq = 0; kq < 4; ++kq) {
-        r[kq] = u32x4{0, 0, 0, 0};
-        if (k0 + 4 * kg + kq < n) r[kq] = *(const u32x4 *)(Vg + (int64_t)(k0 + 4 * kg + kq) * kv_stride + dg * 8);
-      }
+  for (int i = 0; i < KP; ++i) {
+    const int p = tid + i * kThreads;
+    koff[i] = (unsigned)(p / (D / 8)) * row_bytes + (p % (D / 8)) * 16;
+  }
+#pragma unroll
+  for (int i = 0; i < VP; ++i) {
+    const int p = tid + i * kThreads;
+#pragma unroll
+    for (int kq = 0; kq < 4; ++kq) voff[i][kq] = (unsigned)(4 * (p / (D / 8)) + kq) * row_bytes + (p % (D / 8)) * 16;
+  }
+  auto gload = [&](int k0) {
+    const unsigned soff = (unsigned)k0 * row_bytes;
+#pragma unroll
+    for (int i = 0; i < KP; ++i)
+      if (KPIECES % kThreads == 0 || tid + i * kThreads < KPIECES)
+        kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(krsrc, koff[i], soff, 0);
+#pragma unroll
+    for (int i = 0; i < VP; ++i)
+#pragma unroll
+      for (int kq = 0; kq < 4; ++kq)
+        if (VPATCHES % kThreads == 0 || tid + i * kThreads < VPATCHES)
+          vreg[i][kq] = __builtin_amdgcn_raw_buffer_load_b128(vrsrc, voff[i][kq], soff, 0);
+  };
+  auto lstore = [&](char *buf) {
+    char *Ks = buf, *Vt = buf + KS_BYTES;
+#pragma unroll
+    for (int i = 0; i < KP; ++i) {
+      const int p = tid + i * kThreads, row = p / (D / 8), pc = p % (D / 8);
+      if (KPIECES % kThreads == 0 || p < KPIECES) *(u32x4 *)(Ks + (row * KS_STRIDE + pc * 8) * 2) = kreg[i];
+    }
+#pragma unroll
+    for (int i = 0; i < VP; ++i) {
+      const int p = tid + i * kThreads, kg = p / (D / 8), dg = p % (D / 8);
+      if (VPATCHES % kThreads != 0 && p >= VPATCHES) continue;
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
-        u32x2 even = {__builtin_amdgcn_perm(r[1][jj], r[0][jj], 0x05040100u),
-                      __builtin_amdgcn_perm(r[3][jj], r[2][jj], 0x05040100u)};
-        u32x2 odd = {__builtin_amdgcn_perm(r[1][jj], r[0][jj], 0x07060302u),
-                     __builtin_amdgcn_perm(r[3][jj], r[2][jj], 0x07060302u)};
-        *(u32x2 *)(Vt + ((8 * dg + 2 * jj) * VT_STRIDE + 4 * kg) * 2) = even;
-        *(u32x2 *)(Vt + ((8 * dg + 2 * jj + 1) * VT_STRIDE + 4 * kg) * 2) = odd;
+        u32x2 even = {__builtin_amdgcn_perm(vreg[i][1][jj], vreg[i][0][jj], 0x05040100u),
+                      __builtin_amdgcn_perm(vreg[i][3][jj], vreg[i][2][jj], 0x05040100u)};
+        u32x2 odd = {__builtin_amdgcn_perm(vreg[i][1][jj], vreg[i][0][jj], 0x07060302u),
+                     __builtin_amdgcn_perm(vreg[i][3][jj], vreg[i][2][jj], 0x07060302u)};
+        // 8-byte column units are XOR-swizzled with bits of the row so that the 16 lanes of a write
+        // (rows 8 apart) and the 16 lanes of an operand read (consecutive rows) each cover all banks
+        const int unit = kg ^ ((dg >> 1) & 7);
+        *(u32x2 *)(Vt + (8 * dg + 2 * jj) * (VT_STRIDE * 2) + unit * 8) = even;
+        *(u32x2 *)(Vt + (8 * dg + 2 * jj + 1) * (VT_STRIDE * 2) + unit * 8) = odd;
       }
     }
-    __syncthreads();
-    if (CAUSAL && k0 > wq0 + 31) continue;  // every key of the tile is after every query of this wavefront
+  };
 
-    // S^T = K Q^T: rows = keys (two blocks of 32), columns = this wavefront's 32 queries
-    f32x16 sacc[2];
+  gload(0);
+  lstore(smem);
+  // Pin the Q loads in front of the loop.  The compiler would otherwise sink them behind the barrier, and
+  // because memory-wait counters are in-order, every first use of Q inside the loop would then also wait
+  // for the prefetch loads issued in the same iteration, which defeats the prefetch.
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+  for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) sacc[kb][v] = 0.f;
+    for (int kk = 0; kk < KK; ++kk) asm volatile("" : "+v"(qreg[qb][kk]));
+  __syncthreads();
+
+  for (int j = 0; j < ntiles; ++j) {
+    const int k0 = j * BN;
+    const char *Ks = smem + (j & 1) * BUF_BYTES, *Vt = Ks + KS_BYTES;
+    if (j + 1 < ntiles) gload(k0 + BN);
+
+    if (!(CAUSAL && k0 > wq0 + WQ - 1)) {
+      f32x16 sacc[QB][2];
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4 *)(Ks + ((32 * kb + ql) * KS_STRIDE + 16 * kk + 8 * hh) * 2));
-        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[kk], sacc[kb], 0, 0, 0);
-      }
-    }
-    // register v of a lane holds key 8*(v/4) + 4*hh + v%4 of the 32-key block
-    const bool need_mask = (CAUSAL && k0 + BN - 1 > wq0) || (k0 + BN > n);
-    if (need_mask) {
+      for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) sacc[qb][kb][v] = 0.f;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int key = k0 + 32 * kb + 8 * (v / 4) + 4 * hh + (v % 4);
-          if ((CAUSAL && key > my_q) || key >= n) sacc[kb][v] = -INFINITY;
+        for (int kk = 0; kk < KK; ++kk) {
+          const bf16x8 a =
+              __builtin_bit_cast(bf16x8, *(const u32x4 *)(Ks + ((32 * kb + ql) * KS_STRIDE + 16 * kk + 8 * hh) * 2));
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb)
+            sacc[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qb][kk], sacc[qb][kb], 0, 0, 0);
+        }
+      const bool need_mask = (CAUSAL && k0 + BN - 1 > wq0) || (k0 + BN > n);
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        const int my_q = wq0 + 32 * qb + ql;
+        if (need_mask) {
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int key = k0 + 32 * kb + 8 * (v / 4) + 4 * hh + (v % 4);
+              if ((CAUSAL && key > my_q) || key >= n) sacc[qb][kb][v] = -INFINITY;
+            }
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[qb][kb][v]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m[qb], mx);
+        const float ms = (m_new == -INFINITY ? 0.f : m_new) * scale_log2e;
+        const float alpha = __builtin_amdgcn_exp2f(m[qb] * scale_log2e - ms);
+        const bool grew = m_new > m[qb];
+        m[qb] = m_new;
+        float psum = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][v], scale_log2e, -ms));
+            sacc[qb][kb][v] = p;
+            psum += p;
+          }
+        lsum[qb] = lsum[qb] * alpha + psum;
+        if (__any(grew)) {  // once the running maxima have settled the accumulators need no rescaling
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) oacc[qb][db][v] *= alpha;
+        }
+      }
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          bf16x8 pb[QB];
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb) {
+            u32x4 pw;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              pw[e] = pack_bf16(sacc[qb][kb][8 * half + 2 * e], sacc[qb][kb][8 * half + 2 * e + 1]);
+            pb[qb] = __builtin_bit_cast(bf16x8, pw);
+          }
+#pragma unroll
+          for (int db = 0; db < DB; ++db) {
+            const int sw = (2 * db + (ql >> 4)) & 7, unit = 8 * kb + 4 * half + hh;
+            const char *vrow = Vt + (32 * db + ql) * (VT_STRIDE * 2);
+            const u32x2 lo = *(const u32x2 *)(vrow + ((unit ^ sw) * 8)), hi = *(const u32x2 *)(vrow + (((unit + 2) ^ sw) * 8));
+            const bf16x8 a = __builtin_bit_cast(bf16x8, u32x4{lo.x, lo.y, hi.x, hi.y});
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+              oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qb], oacc[qb][db], 0, 0, 0);
+          }
         }
     }
-    float mx = -INFINITY;
+    if (j + 1 < ntiles) lstore(smem + ((j + 1) & 1) * BUF_BYTES);
+    __syncthreads();
+  }
+
+  // K/V tiles are dead (the loop ended on a barrier); reuse LDS to turn O^T into row-major rows
+  char *Os = smem + wave * (WQ * OS_STRIDE * 2);
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[kb][v]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m, mx);
-    const float ms = (m_new == -INFINITY ? 0.f : m_new) * scale_log2e;
-    const float alpha = __builtin_amdgcn_exp2f(m * scale_log2e - ms);
-    m = m_new;
-    float psum = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb][v], scale_log2e, -ms));
-        sacc[kb][v] = p;
-        psum += p;
-      }
-    lsum = lsum * alpha + psum;
+  for (int qb = 0; qb < QB; ++qb) {
+    float l = lsum[qb];
+    l += __shfl_xor(l, 32);
+    const float inv = l > 0.f ? 1.f / l : 0.f;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
-
-    // O^T += V^T P^T, 16 keys per step
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        u32x4 pw;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) pw[e] = pack_bf16(sacc[kb][8 * half + 2 * e], sacc[kb][8 * half + 2 * e + 1]);
-        const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const char *vp = Vt + ((32 * db + ql) * VT_STRIDE + 32 * kb + 16 * half + 4 * hh) * 2;
-          u32x2 lo = *(const u32x2 *)vp, hi = *(const u32x2 *)(vp + 16);
-          u32x4 aw = {lo.x, lo.y, hi.x, hi.y};
-          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aw), pb, oacc[db], 0, 0, 0);
-        }
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int d0 = 32 * db + 8 * q4 + 4 * hh;
+        u32x2 w = {pack_bf16(oacc[qb][db][4 * q4] * inv, oacc[qb][db][4 * q4 + 1] * inv),
+                   pack_bf16(oacc[qb][db][4 * q4 + 2] * inv, oacc[qb][db][4 * q4 + 3] * inv)};
+        *(u32x2 *)(Os + ((32 * qb + ql) * OS_STRIDE + d0) * 2) = w;
       }
   }
-
-  lsum += __shfl_xor(lsum, 32);
-  const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
-  __syncthreads();  // K/V tiles are dead; reuse LDS to turn O^T into row-major rows
-  char *Os = smem + wave * (32 * OS_STRIDE * 2);
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-      const int d0 = 32 * db + 8 * q4 + 4 * hh;
-      u32x2 w = {pack_bf16(oacc[db][4 * q4] * inv, oacc[db][4 * q4 + 1] * inv),
-                 pack_bf16(oacc[db][4 * q4 + 2] * inv, oacc[db][4 * q4 + 3] * inv)};
-      *(u32x2 *)(Os + (ql * OS_STRIDE + d0) * 2) = w;
-    }
   __syncthreads();
-  for (int p = lane; p < 32 * (D / 8); p += 64) {
+  for (int p = lane; p < WQ * (D / 8); p += 64) {
     const int row = p / (D / 8), pc = p % (D / 8);
     if (wq0 + row < n)
       *(u32x4 *)(O + (t0 + wq0 + row) * q_stride + (int64_t)h * D + pc * 8) =
@@ -274,18 +353,21 @@ prefill_f32_kernel(const float *__restrict__ Q, const float *__restrict__ K, con
 template <int D>
 hipError_t launch_bf16(const lkv_ctx *c, const void *Q, const void *K, const void *V, void *O, const int32_t *cu,
                        int num_seqs, int max_seqlen, int causal, hipStream_t s) {
-  const int tiles = (max_seqlen + BM - 1) / BM;
+  constexpr int QB = 1, BMQ = 128 * QB;
+  // the kernel addresses a sequence's K/V rows with 32-bit byte offsets
+  if ((int64_t)max_seqlen * c->cfg.num_kv_heads * D * 2 >= ((int64_t)1 << 32)) return hipErrorInvalidValue;
+  const int tiles = (max_seqlen + BMQ - 1) / BMQ;
   const int64_t total = (int64_t)tiles * c->cfg.num_q_heads * num_seqs;
   if (total > INT32_MAX - kXcds) return hipErrorInvalidValue;
   const int per_xcd = (int)((total + kXcds - 1) / kXcds);
   const float sl2 = c->scale * kLog2e;
   dim3 grid((unsigned)(per_xcd * kXcds));
   if (causal)
-    hipLaunchKernelGGL((prefill_bf16_kernel<D, true>), grid, dim3(kThreads), 0, s, (const uint16_t *)Q,
+    hipLaunchKernelGGL((prefill_bf16_kernel<D, true, QB>), grid, dim3(kThreads), 0, s, (const uint16_t *)Q,
                        (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, cu, c->cfg.num_q_heads,
                        c->cfg.num_kv_heads, tiles, (int)total, sl2);
   else
-    hipLaunchKernelGGL((prefill_bf16_kernel<D, false>), grid, dim3(kThreads), 0, s, (const uint16_t *)Q,
+    hipLaunchKernelGGL((prefill_bf16_kernel<D, false, QB>), grid, dim3(kThreads), 0, s, (const uint16_t *)Q,
                        (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, cu, c->cfg.num_q_heads,
                        c->cfg.num_kv_heads, tiles, (int)total, sl2);
   return hipGetLastError();
