@@ -124,29 +124,26 @@ def main():
     dv = [randn(B, sh.num_kv_heads, sh.head_dim) for _ in range(L)]
     dO = torch.empty_like(dq[0])
     off_layers = list(w.offload_layers)
-    pinned = {l: [eng.pinned(wl.blocks_for(n, sh.block_size) * sh.block_bytes) for n in w.prompt_lens]
-              for l in off_layers}
     layer_bytes = sum(wl.blocks_for(n, sh.block_size) for n in w.prompt_lens) * sh.block_bytes
+    pinned = {l: eng.pinned(layer_bytes) for l in off_layers}
 
     def step():
         eng.reset()
         eng.begin_prompts(w.prompt_lens)
-        for l in range(L):
-            i = l % n_in
-            eng.prefill_layer(l, Qs[i], Ks[i], Vs[i], O, offload_to=pinned.get(l))
+        eng.prefill_all_layers(Qs, Ks, Vs, O, pinned)
         for l in off_layers:
             eng.release_offloaded(l)
         for l in off_layers:
             eng.reload_layer(l)
         for st in range(w.decode_steps):
-            for l in range(L):
-                eng.decode_layer(l, dq[l], dk[l], dv[l], dO, step=st)
+            eng.decode_all_layers(dq, dk, dv, dO, step=st)
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
     eng.timing = True
     eng.timers.clear()
+    eng.ctx.set_profiling(True)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
@@ -154,6 +151,8 @@ def main():
     wall = time.perf_counter() - t0
     ms = eng.elapsed_ms()
     eng.timing = False
+    stats = eng.ctx.get_stats()
+    eng.ctx.set_profiling(False)
 
     K = args.steps
     def total(name):
@@ -169,6 +168,8 @@ def main():
     pf_flops = causal_flops(w.prompt_lens, sh.num_q_heads, sh.head_dim)
     prefill_tflops = pf_flops / (avg("prefill_attention") * 1e-3) / 1e12
     write_gbs = 2 * T * sh.token_bytes / (avg("write_kv") * 1e-3) / 1e9
+    pack_gbs = stats["pack_kernel_bytes"] / max(stats["pack_kernel_ns"], 1)      # bytes/ns = GB/s
+    unpack_gbs = stats["unpack_kernel_bytes"] / max(stats["unpack_kernel_ns"], 1)
 
     def span_ms(name):  # first start -> last end of a side-stream activity, per step
         v = eng.timers.get(name, [])
@@ -184,6 +185,55 @@ def main():
     pf_overlap = [t for i, t in enumerate(pf) if i % L > first_off]
     off_gbs = layer_bytes * len(off_layers) / (off_ms * 1e-3) / 1e9 if off_layers else None
     rel_gbs = layer_bytes * len(off_layers) / (rel_ms * 1e-3) / 1e9 if off_layers else None
+
+    # ---- outside the timed steps: the host link's own peak, and how much of the offload hides behind prefill
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+    link = {}
+    big = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    big_host = eng.pinned(1 << 30)
+    for name, dst, src in (("d2h", big_host, big), ("h2d", big, big_host)):
+        dst.copy_(src, non_blocking=True)
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(2):
+            dst.copy_(src, non_blocking=True)
+        b.record()
+        torch.cuda.synchronize()
+        link[name] = 2 * (1 << 30) / (a.elapsed_time(b) * 1e-3) / 1e9
+    del big, big_host
+
+    def prefill_phase(offload):
+        eng.reset()
+        eng.begin_prompts(w.prompt_lens)
+        a, b, d = ev(), ev(), ev()
+        a.record(eng.main)
+        eng.prefill_all_layers(Qs, Ks, Vs, O, pinned if offload else {})
+        b.record(eng.main)
+        d.record(eng.d2h)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b), max(a.elapsed_time(b), a.elapsed_time(d))
+    overlap = None
+    if off_layers:
+        prefill_phase(False)
+        t_compute, _ = prefill_phase(False)
+        a, b = ev(), ev()
+        a.record(eng.d2h)
+        for l in off_layers:
+            eng.offload_layer(l, pinned[l])
+        b.record(eng.d2h)
+        torch.cuda.synchronize()
+        t_link = a.elapsed_time(b)
+        _, t_both = prefill_phase(True)
+        # only the compute issued after the first offload can hide anything
+        t_hideable = t_compute * (L - 1 - first_off) / L
+        overlap = {"prefill_compute_ms": round(t_compute, 3), "offload_link_ms": round(t_link, 3),
+                   "both_ms": round(t_both, 3),
+                   "hidden_frac": round(max(0.0, 1 - (t_both - t_compute) / t_link), 4),
+                   "bound": round(min(1.0, t_hideable / t_link), 4),
+                   "note": "hidden = 1 - (wall(prefill with offload) - wall(prefill alone)) / wall(offload alone); bound = "
+                           "compute issued after the first offload starts / link time: attention-only compute cannot "
+                           "hide a PCIe transfer of the same layers"}
 
     out = {
         "metric": METRIC, "value": round(decode_gbs, 2), "unit": "GB/s",
@@ -205,19 +255,29 @@ def main():
             "prefill_ms_per_layer_copy_running": round(sum(pf_overlap) / max(len(pf_overlap), 1), 4),
             "write_kv_GBps": round(write_gbs, 2),
             "write_kv_us_per_layer": round(avg("write_kv") * 1e3, 2),
+            "pack_kernel_GBps": round(pack_gbs, 2), "unpack_kernel_GBps": round(unpack_gbs, 2),
             "offload_GBps": None if off_gbs is None else round(off_gbs, 2),
             "reload_GBps": None if rel_gbs is None else round(rel_gbs, 2),
             "offload_ms_total": None if off_gbs is None else round(off_ms, 2),
             "reload_ms_total": None if rel_gbs is None else round(rel_ms, 2),
+            "pinned_copy_peak_GBps": {k: round(v, 2) for k, v in link.items()},
+            "offload_frac_of_link_peak": None if off_gbs is None else round(off_gbs / link["d2h"], 4),
+            "reload_frac_of_link_peak": None if rel_gbs is None else round(rel_gbs / link["h2d"], 4),
         },
+        "overlap": overlap,
         "roofline": {"kernel": "prefill_bf16_kernel (lkv_prefill_attention)", "bound": "mfma",
                      "achieved": round(prefill_tflops, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(prefill_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None},
+                     "frac": round(prefill_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "launch_ms": round(avg("prefill_attention"), 4), "flops_per_launch": pf_flops},
         "rooflines_other": {
             "decode": {"bound": "hbm", "achieved": round(decode_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                        "frac": round(decode_gbs / HBM_PEAK_GBS, 4)},
             "write_kv": {"bound": "hbm", "achieved": round(write_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": round(write_gbs / HBM_PEAK_GBS, 4)},
+            "pack": {"bound": "hbm", "achieved": round(pack_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(pack_gbs / HBM_PEAK_GBS, 4)},
+            "unpack": {"bound": "hbm", "achieved": round(unpack_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                       "frac": round(unpack_gbs / HBM_PEAK_GBS, 4)},
         },
     }
     eng.close()

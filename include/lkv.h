@@ -100,6 +100,11 @@ typedef struct {
   int64_t decode_calls;
   int64_t pack_calls, pack_bytes;             /* bytes gathered out of the pool = bytes sent to host */
   int64_t unpack_calls, unpack_bytes;
+  /* filled only while kernel profiling is on (lkv_set_profiling): time the gather / scatter kernels of
+   * pack / unpack spent on the GPU (HIP events on the stream they ran on), and the bytes they moved
+   * (read + write) in those launches */
+  int64_t pack_kernel_ns, pack_kernel_bytes;
+  int64_t unpack_kernel_ns, unpack_kernel_bytes;
 } lkv_stats;
 
 /* ------------------------------------------------------------------ life cycle */
@@ -190,8 +195,12 @@ lkv_status lkv_paged_decode_attention(lkv_ctx *ctx, int32_t layer, const void *Q
 lkv_status lkv_stream_wait_event(lkv_ctx *ctx, int32_t layer, int32_t ev, void *stream);
 /* Blocks the host until that event has happened. */
 lkv_status lkv_event_synchronize(lkv_ctx *ctx, int32_t layer, int32_t ev);
-/* Copies min(size, sizeof(lkv_stats)) bytes of counters to out (host). */
-lkv_status lkv_get_stats(const lkv_ctx *ctx, lkv_stats *out, int64_t size);
+/* Turns per-launch HIP-event timing of the pack / unpack kernels on or off (off by default; each
+ * timed launch costs two extra event records).  Results accumulate in lkv_stats. */
+lkv_status lkv_set_profiling(lkv_ctx *ctx, int32_t on);
+/* Copies min(size, sizeof(lkv_stats)) bytes of counters to out (host).  With profiling on this waits
+ * for the timed launches recorded so far. */
+lkv_status lkv_get_stats(lkv_ctx *ctx, lkv_stats *out, int64_t size);
 
 #ifdef __cplusplus
 }

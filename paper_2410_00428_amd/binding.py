@@ -32,7 +32,7 @@ EXPORTS = (
     "lkv_plan_retained_layers",
     "lkv_write_kv", "lkv_prefill_attention", "lkv_pack_layer_blocks", "lkv_unpack_layer_blocks",
     "lkv_paged_decode_attention",
-    "lkv_stream_wait_event", "lkv_event_synchronize", "lkv_get_stats",
+    "lkv_stream_wait_event", "lkv_event_synchronize", "lkv_set_profiling", "lkv_get_stats",
 )
 
 
@@ -46,7 +46,8 @@ class LkvConfig(ctypes.Structure):
 class LkvStats(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int64) for n in
                 ("write_kv_calls", "write_kv_bytes", "prefill_calls", "decode_calls", "pack_calls", "pack_bytes",
-                 "unpack_calls", "unpack_bytes")]
+                 "unpack_calls", "unpack_bytes", "pack_kernel_ns", "pack_kernel_bytes", "unpack_kernel_ns",
+                 "unpack_kernel_bytes")]
 
 
 class LkvError(RuntimeError):
@@ -98,6 +99,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "lkv_paged_decode_attention": (i32, [vp, i32, vp, vp, vp, i32, vp, i32, vp]),
         "lkv_stream_wait_event": (i32, [vp, i32, i32, vp]),
         "lkv_event_synchronize": (i32, [vp, i32, i32]),
+        "lkv_set_profiling": (i32, [vp, i32]),
         "lkv_get_stats": (i32, [vp, P(LkvStats), i64]),
     }
     for name, (res, args) in sig.items():
@@ -262,6 +264,9 @@ class LKV:
 
     def event_synchronize(self, layer: int, ev: int) -> None:
         self._check(self.lib.lkv_event_synchronize(self.h, layer, ev))
+
+    def set_profiling(self, on: bool) -> None:
+        self._check(self.lib.lkv_set_profiling(self.h, int(bool(on))))
 
     def get_stats(self) -> dict:
         s = LkvStats()

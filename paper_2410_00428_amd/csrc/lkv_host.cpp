@@ -54,6 +54,7 @@ lkv_status staging_create(lkv_ctx *c, lkv::Staging &st) {
   LKV_HIP(c, hipHostMalloc((void **)&st.ids_pinned, ids_bytes, hipHostMallocDefault));
   for (auto &e : st.slot_done) LKV_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
   LKV_HIP(c, hipEventCreateWithFlags(&st.buf_free, hipEventDisableTiming));
+  for (auto &e : st.copy_done) LKV_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
   return LKV_OK;
 }
 
@@ -64,6 +65,8 @@ void staging_destroy(lkv::Staging &st) {
   for (auto &e : st.slot_done)
     if (e) (void)hipEventDestroy(e);
   if (st.buf_free) (void)hipEventDestroy(st.buf_free);
+  for (auto &e : st.copy_done)
+    if (e) (void)hipEventDestroy(e);
   st = lkv::Staging{};
 }
 
@@ -82,11 +85,52 @@ lkv_status stage_ids(lkv_ctx *c, lkv::Staging &st, const int32_t *ids, int64_t n
   return LKV_OK;
 }
 
+// Host-link copies are paced: with a deep backlog of queued copies the runtime was measured to move
+// later ones at a quarter of the link rate, so the host waits until at most kMaxInFlight are queued.
+lkv_status pace_copy(lkv_ctx *c, lkv::Staging &st) {
+  if (st.copies_issued >= lkv::Staging::kMaxInFlight)
+    LKV_HIP(c, hipEventSynchronize(st.copy_done[(st.copies_issued - lkv::Staging::kMaxInFlight) % lkv::Staging::kCopyRing]));
+  return LKV_OK;
+}
+lkv_status copy_issued(lkv_ctx *c, lkv::Staging &st, hipStream_t s) {
+  LKV_HIP(c, hipEventRecord(st.copy_done[st.copies_issued % lkv::Staging::kCopyRing], s));
+  st.copies_issued += 1;
+  return LKV_OK;
+}
+
 lkv_status check_ids(const lkv_ctx *c, const int32_t *ids, int64_t n) {
   for (int64_t i = 0; i < n; ++i)
     if (ids[i] < 0 || ids[i] >= c->cfg.num_pool_blocks)
       return fail(c, LKV_ERR_INVALID_ARG, "block_ids[%lld] = %d is outside the pool (%lld blocks)",
                   (long long)i, ids[i], (long long)c->cfg.num_pool_blocks);
+  return LKV_OK;
+}
+
+// Kernel profiling: brackets one launch with timing events taken from a small free list.
+lkv_status timed_begin(lkv_ctx *c, hipStream_t s, hipEvent_t *a) {
+  *a = nullptr;
+  if (!c->profiling) return LKV_OK;
+  if (c->spare_events.empty()) {
+    LKV_HIP(c, hipEventCreate(a));
+  } else {
+    *a = c->spare_events.back();
+    c->spare_events.pop_back();
+  }
+  LKV_HIP(c, hipEventRecord(*a, s));
+  return LKV_OK;
+}
+
+lkv_status timed_end(lkv_ctx *c, hipStream_t s, hipEvent_t a, int64_t bytes, bool unpack) {
+  if (!a) return LKV_OK;
+  hipEvent_t b;
+  if (c->spare_events.empty()) {
+    LKV_HIP(c, hipEventCreate(&b));
+  } else {
+    b = c->spare_events.back();
+    c->spare_events.pop_back();
+  }
+  LKV_HIP(c, hipEventRecord(b, s));
+  c->timed.push_back({a, b, bytes, unpack});
   return LKV_OK;
 }
 
@@ -186,6 +230,11 @@ void lkv_destroy(lkv_ctx *c) {
   staging_destroy(c->h2d);
   for (auto &ev : c->events)
     if (ev) (void)hipEventDestroy(ev);
+  for (auto &t : c->timed) {
+    (void)hipEventDestroy(t.a);
+    (void)hipEventDestroy(t.b);
+  }
+  for (auto &e : c->spare_events) (void)hipEventDestroy(e);
   if (c->ws) (void)hipFree(c->ws);
   if (c->owns_pool && c->pool) (void)hipFree(c->pool);
   delete c;
@@ -388,12 +437,17 @@ lkv_status lkv_pack_layer_blocks(lkv_ctx *c, int32_t layer, const int32_t *block
     int slot;
     if (lkv_status st = stage_ids(c, sg, block_ids + first, m, s, &slot)) return st;
     if (sg.buf_used) LKV_HIP(c, hipStreamWaitEvent(s, sg.buf_free, 0));
+    hipEvent_t t0;
+    if (lkv_status st = timed_begin(c, s, &t0)) return st;
     LKV_HIP(c, lkv::launch_gather_blocks(c, sg.ids_dev + (size_t)slot * c->staging_blocks, m, sg.buf, s));
+    if (lkv_status st = timed_end(c, s, t0, 2 * m * c->block_bytes, false)) return st;
     LKV_HIP(c, hipEventRecord(sg.slot_done[slot], s));
     if (first + m == n)
       if (lkv_status st = record_event(c, layer, LKV_EV_PACKED, s)) return st;
+    if (lkv_status st = pace_copy(c, sg)) return st;
     LKV_HIP(c, hipMemcpyAsync((char *)pinned_dst + first * c->block_bytes, sg.buf, (size_t)(m * c->block_bytes),
                               hipMemcpyDeviceToHost, s));
+    if (lkv_status st = copy_issued(c, sg, s)) return st;
     LKV_HIP(c, hipEventRecord(sg.buf_free, s));
     sg.buf_used = true;
   }
@@ -418,9 +472,14 @@ lkv_status lkv_unpack_layer_blocks(lkv_ctx *c, int32_t layer, const int32_t *blo
     int slot;
     if (lkv_status st = stage_ids(c, sg, block_ids + first, m, s, &slot)) return st;
     if (sg.buf_used) LKV_HIP(c, hipStreamWaitEvent(s, sg.buf_free, 0));
+    if (lkv_status st = pace_copy(c, sg)) return st;
     LKV_HIP(c, hipMemcpyAsync(sg.buf, (const char *)pinned_src + first * c->block_bytes, (size_t)(m * c->block_bytes),
                               hipMemcpyHostToDevice, s));
+    if (lkv_status st = copy_issued(c, sg, s)) return st;
+    hipEvent_t t0;
+    if (lkv_status st = timed_begin(c, s, &t0)) return st;
     LKV_HIP(c, lkv::launch_scatter_blocks(c, sg.ids_dev + (size_t)slot * c->staging_blocks, m, sg.buf, s));
+    if (lkv_status st = timed_end(c, s, t0, 2 * m * c->block_bytes, true)) return st;
     LKV_HIP(c, hipEventRecord(sg.slot_done[slot], s));
     LKV_HIP(c, hipEventRecord(sg.buf_free, s));
     sg.buf_used = true;
@@ -478,8 +537,31 @@ lkv_status lkv_event_synchronize(lkv_ctx *c, int32_t layer, int32_t ev) {
   return LKV_OK;
 }
 
-lkv_status lkv_get_stats(const lkv_ctx *c, lkv_stats *out, int64_t size) {
+lkv_status lkv_set_profiling(lkv_ctx *c, int32_t on) {
+  if (!c) return LKV_ERR_INVALID_ARG;
+  if (c->logical_only) return fail(c, LKV_ERR_DEVICE, "lkv_set_profiling: this context has no device resources");
+  c->profiling = on != 0;
+  return LKV_OK;
+}
+
+lkv_status lkv_get_stats(lkv_ctx *c, lkv_stats *out, int64_t size) {
   if (!c || !out || size < 0) return LKV_ERR_INVALID_ARG;
+  for (auto &t : c->timed) {
+    LKV_HIP(c, hipEventSynchronize(t.b));
+    float ms = 0.f;
+    LKV_HIP(c, hipEventElapsedTime(&ms, t.a, t.b));
+    const int64_t ns = (int64_t)((double)ms * 1e6);
+    if (t.unpack) {
+      c->stats.unpack_kernel_ns += ns;
+      c->stats.unpack_kernel_bytes += t.bytes;
+    } else {
+      c->stats.pack_kernel_ns += ns;
+      c->stats.pack_kernel_bytes += t.bytes;
+    }
+    c->spare_events.push_back(t.a);
+    c->spare_events.push_back(t.b);
+  }
+  c->timed.clear();
   size_t n = (size_t)size < sizeof(lkv_stats) ? (size_t)size : sizeof(lkv_stats);
   std::memcpy(out, &c->stats, n);
   return LKV_OK;

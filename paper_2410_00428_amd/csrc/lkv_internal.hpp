@@ -38,6 +38,10 @@ struct Staging {
   int next_slot = 0;
   hipEvent_t buf_free = nullptr;  // last user of buf has finished with it
   bool buf_used = false;
+  // pacing: at most kMaxInFlight host-link copies of this direction are queued at any time
+  static constexpr int kCopyRing = 4, kMaxInFlight = 2;
+  hipEvent_t copy_done[kCopyRing] = {};
+  int64_t copies_issued = 0;
 };
 
 }  // namespace lkv
@@ -64,6 +68,15 @@ struct lkv_ctx {
   std::vector<int32_t> free_list;  // stack, back() is handed out next
   std::unordered_map<lkv::LayerKey, lkv::LayerState, lkv::LayerKeyHash> layers;
   lkv_stats stats{};
+  // kernel profiling: (start, stop, bytes, is_unpack) of launches not yet folded into stats
+  struct Timed {
+    hipEvent_t a, b;
+    int64_t bytes;
+    bool unpack;
+  };
+  bool profiling = false;
+  std::vector<Timed> timed;
+  std::vector<hipEvent_t> spare_events;
   mutable std::string err;
 };
 

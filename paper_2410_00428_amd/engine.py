@@ -31,7 +31,7 @@ class LayerKVEngine:
         self.d2h = torch.cuda.Stream(self.device)   # offload stream (default priority)
         self.h2d = torch.cuda.Stream(self.device)   # reload stream
         self.lens: List[int] = []
-        self.host_images: Dict[int, List[torch.Tensor]] = {}   # layer -> pinned image per sequence
+        self.host_images: Dict[int, torch.Tensor] = {}   # layer -> pinned image (all sequences)
         self.timers: Dict[str, list] = {}
         self.timing = False
 
@@ -67,15 +67,19 @@ class LayerKVEngine:
         self.cu_dev = torch.from_numpy(self.cu).to(self.device)
         self.T = int(self.cu[-1])
 
-    def prefill_layer(self, layer: int, Q, K, V, O, offload_to: Optional[List[torch.Tensor]] = None,
-                      attention: bool = True) -> None:
-        """S0 allocate + map, S1 write, S2 attention, then (if asked) S3 offload on the side stream."""
+    def map_prefill_layer(self, layer: int) -> np.ndarray:
+        """S0 for one layer: allocate every prompt's blocks and return the slot of every token."""
         c = self.ctx
         slots = []
         for s, n in enumerate(self.lens):
             c.alloc_layer_blocks(s, layer, n)
             slots.append(c.build_slot_mapping(s, layer, 0, n))
-        slots_dev = torch.from_numpy(np.concatenate(slots)).to(self.device, non_blocking=False)
+        return np.concatenate(slots)
+
+    def launch_prefill_layer(self, layer: int, Q, K, V, O, slots_dev, offload_to: Optional[torch.Tensor] = None,
+                             attention: bool = True) -> None:
+        """S1 write, S2 attention, then (if asked) S3 offload on the side stream."""
+        c = self.ctx
         self._timed("write_kv", self.main, lambda: c.write_kv(layer, K, V, slots_dev, self.T, self.main))
         if attention:
             self._timed("prefill_attention", self.main,
@@ -84,14 +88,33 @@ class LayerKVEngine:
         if offload_to is not None:
             self.offload_layer(layer, offload_to)
 
-    def offload_layer(self, layer: int, bufs: List[torch.Tensor]) -> None:
-        """Pack every sequence's blocks of the layer and send them to pinned memory on the d2h stream."""
-        c = self.ctx
-        def go():
-            for s in range(len(self.lens)):
-                c.pack_layer_blocks(layer, c.get_block_table(s, layer), bufs[s], self.d2h)
-        self._timed("offload", self.d2h, go)
-        self.host_images[layer] = bufs
+    def prefill_layer(self, layer: int, Q, K, V, O, offload_to: Optional[torch.Tensor] = None,
+                      attention: bool = True) -> None:
+        """S0 to S3 for one layer."""
+        slots_dev = torch.from_numpy(self.map_prefill_layer(layer)).to(self.device)
+        self.launch_prefill_layer(layer, Q, K, V, O, slots_dev, offload_to, attention)
+
+    def prefill_all_layers(self, Qs, Ks, Vs, O, offload: Dict[int, torch.Tensor]) -> None:
+        """All layers of a prompt batch: the host-side mapping of every layer first (one upload), then the
+        kernels of all layers back to back, each offloaded layer's copy starting behind its write."""
+        L = self.shape.num_layers
+        slots = np.stack([self.map_prefill_layer(l) for l in range(L)])
+        slots_dev = torch.from_numpy(slots).to(self.device)
+        for l in range(L):
+            i = l % len(Qs)
+            self.launch_prefill_layer(l, Qs[i], Ks[i], Vs[i], O, slots_dev[l], offload.get(l))
+        self._keep_prefill = slots_dev
+
+    def layer_block_ids(self, layer: int) -> np.ndarray:
+        """Block ids of every sequence's table for the layer, sequence after sequence."""
+        return np.concatenate([self.ctx.get_block_table(s, layer) for s in range(len(self.lens))])
+
+    def offload_layer(self, layer: int, buf: torch.Tensor) -> None:
+        """Pack the layer's blocks of all sequences (one call, one image) and send them to pinned
+        memory on the d2h stream."""
+        ids = self.layer_block_ids(layer)
+        self._timed("offload", self.d2h, lambda: self.ctx.pack_layer_blocks(layer, ids, buf, self.d2h))
+        self.host_images[layer] = buf
 
     def release_offloaded(self, layer: int) -> None:
         """The layer's blocks go back to the free list (host logic); the data lives on the host now.
@@ -104,25 +127,32 @@ class LayerKVEngine:
 
     # ------------------------------------------------------------------ reload + decode (S4, S5)
     def reload_layer(self, layer: int, lens: Optional[Sequence[int]] = None) -> None:
+        """Give every sequence fresh blocks for the layer and bring its image back on the h2d stream."""
         c = self.ctx
         lens = lens or self.lens
-        bufs = self.host_images[layer]
+        buf = self.host_images[layer]
         c.stream_wait_event(layer, lkv.LKV_EV_OFFLOADED, self.h2d)   # the image must be complete on the host
-        def go():
-            for s, n in enumerate(lens):
-                c.alloc_layer_blocks(s, layer, n)
-                c.unpack_layer_blocks(layer, c.get_block_table(s, layer), bufs[s], self.h2d)
-        self._timed("reload", self.h2d, go)
+        for s, n in enumerate(lens):
+            c.alloc_layer_blocks(s, layer, n)
+        ids = self.layer_block_ids(layer)
+        self._timed("reload", self.h2d, lambda: c.unpack_layer_blocks(layer, ids, buf, self.h2d))
 
-    def decode_layer(self, layer: int, q, k, v, O, step: int = 0) -> None:
-        """Append one token per sequence to the layer and attend over context n+step+1."""
+    def map_decode_layer(self, layer: int, step: int):
+        """S0 of a decode step for one layer: one more slot per sequence, the layer's padded table."""
         c = self.ctx
         B = len(self.lens)
         slots = np.empty(B, dtype=np.int64)
         for s, n in enumerate(self.lens):
             c.alloc_layer_blocks(s, layer, n + step + 1)
             slots[s] = c.build_slot_mapping(s, layer, n + step, 1)[0]
-        bt = c.padded_block_table(range(B), layer)
+        width = max(blocks_for(n + step + 1, self.shape.block_size) for n in self.lens)
+        return slots, c.padded_block_table(range(B), layer, width)
+
+    def decode_layer(self, layer: int, q, k, v, O, step: int = 0) -> None:
+        """Append one token per sequence to the layer and attend over context n+step+1."""
+        c = self.ctx
+        B = len(self.lens)
+        slots, bt = self.map_decode_layer(layer, step)
         ctx_lens = np.asarray([n + step + 1 for n in self.lens], dtype=np.int32)
         slots_dev = torch.from_numpy(slots).to(self.device)
         bt_dev = torch.from_numpy(bt).to(self.device)
@@ -130,6 +160,22 @@ class LayerKVEngine:
         self._timed("write_kv_decode", self.main, lambda: c.write_kv(layer, k, v, slots_dev, B, self.main))
         self._timed("decode_attention", self.main,
                     lambda: c.paged_decode_attention(layer, q, O, bt_dev, bt.shape[1], cl_dev, B, self.main))
+        self._keep = (slots_dev, bt_dev, cl_dev)
+
+    def decode_all_layers(self, qs, ks, vs, O, step: int = 0) -> None:
+        """One decode step over all layers: every layer's mapping first (one upload of all tables), then
+        write + attention of all layers back to back."""
+        c = self.ctx
+        L, B = self.shape.num_layers, len(self.lens)
+        maps = [self.map_decode_layer(l, step) for l in range(L)]
+        slots_dev = torch.from_numpy(np.stack([m[0] for m in maps])).to(self.device)
+        bt_dev = torch.from_numpy(np.stack([m[1] for m in maps])).to(self.device)
+        width = bt_dev.shape[2]
+        cl_dev = torch.from_numpy(np.asarray([n + step + 1 for n in self.lens], dtype=np.int32)).to(self.device)
+        for l in range(L):
+            self._timed("write_kv_decode", self.main, lambda: c.write_kv(l, ks[l], vs[l], slots_dev[l], B, self.main))
+            self._timed("decode_attention", self.main,
+                        lambda: c.paged_decode_attention(l, qs[l], O, bt_dev[l], width, cl_dev, B, self.main))
         self._keep = (slots_dev, bt_dev, cl_dev)
 
     def close(self) -> None:
