@@ -40,8 +40,17 @@ lkv_status record_event(lkv_ctx *c, int32_t layer, int32_t ev, hipStream_t s) {
 }
 
 lkv_status wait_event(lkv_ctx *c, int32_t layer, int32_t ev, hipStream_t s) {
-  if (c->event_recorded[(size_t)layer * 4 + ev])
-    LKV_HIP(c, hipStreamWaitEvent(s, event_of(c, layer, ev), 0));
+  uint8_t &pending = c->event_recorded[(size_t)layer * 4 + ev];
+  if (!pending) return LKV_OK;
+  // an event that has already happened needs no wait packet in the stream (and is forgotten)
+  hipError_t q = hipEventQuery(event_of(c, layer, ev));
+  if (q == hipSuccess) {
+    pending = 0;
+    return LKV_OK;
+  }
+  if (q != hipErrorNotReady) return fail(c, LKV_ERR_DEVICE, "hipEventQuery failed: %s", hipGetErrorString(q));
+  (void)hipGetLastError();  // "not ready" is an answer, not an error: do not leave it for the next launch check
+  LKV_HIP(c, hipStreamWaitEvent(s, event_of(c, layer, ev), 0));
   return LKV_OK;
 }
 
