@@ -25,6 +25,10 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+# HBM bytes per launch of the dominant kernel (prefill_bf16_kernel) from two rocprofv3 --pmc runs of this
+# command (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for the pack gather
+# kernel, which moves a known 256 MiB each way: see profiles/bench_workload2_hbm_traffic.md
+TRAFFIC_BYTES = {2: 385.4 * 2**20 + 128.0 * 2**20}
 METRIC = "decode paged-attn HBM GB/s; prefill attn TFLOP/s; layer offload/reload GB/s"
 
 
@@ -214,9 +218,12 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b), max(a.elapsed_time(b), a.elapsed_time(d))
     overlap = None
+    iso = {}
     if off_layers:
         prefill_phase(False)
         t_compute, _ = prefill_phase(False)
+        eng.ctx.set_profiling(True)
+        s0 = eng.ctx.get_stats()
         a, b = ev(), ev()
         a.record(eng.d2h)
         for l in off_layers:
@@ -224,6 +231,25 @@ def main():
         b.record(eng.d2h)
         torch.cuda.synchronize()
         t_link = a.elapsed_time(b)
+        s1 = eng.ctx.get_stats()
+        iso["pack_kernel_GBps"] = (s1["pack_kernel_bytes"] - s0["pack_kernel_bytes"]) / max(
+            s1["pack_kernel_ns"] - s0["pack_kernel_ns"], 1)
+        # reload alone: nothing else on the GPU
+        for l in off_layers:
+            eng.release_offloaded(l)
+        a, b = ev(), ev()
+        a.record(eng.h2d)
+        for l in off_layers:
+            eng.reload_layer(l)
+        b.record(eng.h2d)
+        torch.cuda.synchronize()
+        t_reload = a.elapsed_time(b)
+        s2 = eng.ctx.get_stats()
+        eng.ctx.set_profiling(False)
+        iso["unpack_kernel_GBps"] = (s2["unpack_kernel_bytes"] - s1["unpack_kernel_bytes"]) / max(
+            s2["unpack_kernel_ns"] - s1["unpack_kernel_ns"], 1)
+        iso["offload_GBps"] = layer_bytes * len(off_layers) / (t_link * 1e-3) / 1e9
+        iso["reload_GBps"] = layer_bytes * len(off_layers) / (t_reload * 1e-3) / 1e9
         _, t_both = prefill_phase(True)
         # only the compute issued after the first offload can hide anything
         t_hideable = t_compute * (L - 1 - first_off) / L
@@ -234,6 +260,35 @@ def main():
                    "note": "hidden = 1 - (wall(prefill with offload) - wall(prefill alone)) / wall(offload alone); bound = "
                            "compute issued after the first offload starts / link time: attention-only compute cannot "
                            "hide a PCIe transfer of the same layers"}
+
+    # kernels alone, launched back to back (no other stream active, no events between launches)
+    def alone(fn, launches, reps=3):
+        fn()
+        torch.cuda.synchronize()
+        a, b = ev(), ev()
+        a.record(eng.main)
+        for _ in range(reps):
+            fn()
+        b.record(eng.main)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / (reps * launches)
+    eng.reset()
+    eng.begin_prompts(w.prompt_lens)
+    slots_all = torch.from_numpy(np.stack([eng.map_prefill_layer(l) for l in range(L)])).to(dev)
+    c = eng.ctx
+    t_write = alone(lambda: [c.write_kv(l, Ks[l % n_in], Vs[l % n_in], slots_all[l], T, eng.main) for l in range(L)], L)
+    t_prefill = alone(lambda: [c.prefill_attention(l, Qs[l % n_in], Ks[l % n_in], Vs[l % n_in], O, eng.cu_dev, B,
+                                                   max(w.prompt_lens), T, True, eng.main) for l in range(L)], L)
+    maps = [eng.map_decode_layer(l, 0) for l in range(L)]
+    bt_all = torch.from_numpy(np.stack([m[1] for m in maps])).to(dev)
+    cl_dev = torch.from_numpy(np.asarray([n + 1 for n in w.prompt_lens], dtype=np.int32)).to(dev)
+    t_decode = alone(lambda: [c.paged_decode_attention(l, dq[l], dO, bt_all[l], bt_all.shape[2], cl_dev, B, eng.main)
+                              for l in range(L)], L, reps=5)
+    iso["write_kv_GBps"] = 2 * T * sh.token_bytes / (t_write * 1e-3) / 1e9
+    iso["prefill_attn_TFLOPs"] = pf_flops / (t_prefill * 1e-3) / 1e12
+    iso["decode_paged_attn_GBps"] = decode_bytes_per_launch[0] / (t_decode * 1e-3) / 1e9
+    iso = {k: round(v, 2) for k, v in iso.items()}
+    traffic = TRAFFIC_BYTES.get(args.workload)
 
     out = {
         "metric": METRIC, "value": round(decode_gbs, 2), "unit": "GB/s",
@@ -265,9 +320,11 @@ def main():
             "reload_frac_of_link_peak": None if rel_gbs is None else round(rel_gbs / link["h2d"], 4),
         },
         "overlap": overlap,
+        "kernels_alone": dict(iso, note="each kernel launched back to back with nothing else on the GPU; the "
+                                        "components above are measured inside the full step, where streams overlap"),
         "roofline": {"kernel": "prefill_bf16_kernel (lkv_prefill_attention)", "bound": "mfma",
                      "achieved": round(prefill_tflops, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(prefill_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "frac": round(prefill_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic,
                      "launch_ms": round(avg("prefill_attention"), 4), "flops_per_launch": pf_flops},
         "rooflines_other": {
             "decode": {"bound": "hbm", "achieved": round(decode_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
