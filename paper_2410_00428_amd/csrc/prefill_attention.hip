@@ -1,18 +1,27 @@
 // Prefill attention over packed variable-length prompts (paper Section 2.1.1: all prompt tokens
 // are processed in parallel; the attention cost is quadratic in the prompt length).
 //
-// bf16 path: the only dense contraction of the library, so it runs on the gfx950 matrix cores
-// (v_mfma_f32_32x32x16_bf16, fp32 accumulation).  A workgroup of four wavefronts owns 128
-// consecutive queries of one (sequence, q head); each wavefront owns 32 of them and keeps its
-// slice of Q in registers for the whole kernel.  Keys/values stream through LDS in tiles of 64.
-// Scores are computed TRANSPOSED, S^T = K Q^T, so that after the MFMA every lane holds the
-// scores of ONE query (its column) for 16 keys per 32-key block: the softmax row reductions are
-// in-lane plus one exchange with the lane 32 away, and the exponentiated scores are already laid
-// out as the B operand of the second product O^T = V^T P^T.  For that product the contraction
-// index (key) of a lane's 8 elements is k(h,e) = 8*(e/4) + 4*h + e%4 within a 16-key slab; V is
-// transposed on its way into LDS so the A operand reads those keys as two 8-byte words.
-// Probabilities are rounded to bf16 for the second product; the row sum uses the fp32 values.
-// Causal tiles above the diagonal are skipped, only tiles that touch it are masked.
+// bf16, head_dim 128 (the shape of every bf16 workload): the only dense contraction of the library, so it runs
+// on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation).  A workgroup of four wavefronts owns
+// 128 consecutive queries of one (sequence, q head); each wavefront owns 32 of them and keeps its slice of Q in
+// registers.  Keys and values stream through LDS in units of 32 keys:
+//   * global -> LDS goes through `buffer_load_dwordx4 ... lds` (no registers, no LDS store instructions); a
+//     unit is stored row-major, its 16-byte pieces XOR-swizzled so that every operand read is bank-conflict
+//     free; four units of K and four of V are in flight or in use at any time (64 KiB, two workgroups per CU);
+//   * scores are computed TRANSPOSED, S^T = K Q^T, so that after the MFMA every lane holds the scores of ONE
+//     query (its column) for 16 of the 32 keys: the softmax row reductions are in-lane plus one
+//     v_permlane32_swap, and the exponentiated scores are already laid out as the B operand of the second
+//     product O^T = V^T P^T;
+//   * the A operand of that product is V^T, which is read straight out of the row-major unit with the
+//     transposing LDS load ds_read_b64_tr_b16;
+//   * the loop is software-pipelined over units: the score MFMAs of unit u+1 are issued before the softmax of
+//     unit u, and the first operands of unit u+2 are fetched from LDS before the barrier that ends unit u.
+// Probabilities are rounded to bf16 for the second product; the row sum uses the fp32 values.  Under the causal
+// mask a workgroup handles query tile T-1-p and then tile p of its head, whose key ranges add up to the same
+// length for every p: all workgroups of a launch cost the same.  Units above the diagonal are skipped, only
+// the unit that touches it is masked.
+//
+// bf16, head_dim 64: the earlier register-staged kernel (64-key tiles, V transposed on its way into LDS).
 //
 // f32 path: plain fp32 vector arithmetic (sizes where this runs are launch-bound), one query per
 // four lanes, keys/values through LDS.
@@ -292,6 +301,323 @@ prefill_bf16_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__
   }
 }
 
+// ------------------------------------------------------------------------------------------ bf16, d = 128
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) char lds_char;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+// max / sum of a value and the value held by the lane 32 away (same result in both lanes)
+__device__ __forceinline__ float both_max(float x) {
+  auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+}
+__device__ __forceinline__ float both_sum(float x) {
+  auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+}
+
+// 16 bytes per lane from a buffer straight into LDS at lds_addr + lane*16 (lds_addr is wave-uniform).  Issued
+// through inline asm so that the compiler does not tie later LDS reads to these loads: the kernel waits for them
+// explicitly (vmcnt) before the barrier that publishes a unit.
+// (m0 carries the LDS address of such a load; the compiler itself never keeps a value in m0 in this file)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, unsigned lds_addr, unsigned voffset, unsigned soffset) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :
+               : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset)
+               : "memory", "m0");
+}
+#pragma clang diagnostic pop
+constexpr int kVmcnt0 = 0x0F70;  // s_waitcnt vmcnt(0), other counters untouched
+constexpr int kVmcnt6 = 0x0F76;  // s_waitcnt vmcnt(6)
+
+template <bool CAUSAL>
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+prefill_bf16_d128_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
+                         uint16_t *__restrict__ O, const int32_t *__restrict__ cu_seqlens, int Hq, int Hkv,
+                         int tiles_per_seq, int pairs, float scale_log2e) {
+  constexpr int D = 128, UK = 32, KR = 4, VR = 4, TB = UK * D * 2, VOFF = KR * TB;
+  constexpr int BMQ = 128, WQ = 32, OS_STRIDE = D + 8;
+  __shared__ __attribute__((aligned(1024))) char smem[(KR + VR) * TB];
+
+  // Workgroup order.  Each XCD (blockIdx.x % 8) owns a contiguous range of (sequence, head) pairs so that the
+  // query tiles of a head share that XCD's L2; a workgroup takes tile T-1-p and then tile p of its pair.
+  const int ppx = (pairs + kXcds - 1) / kXcds;
+  const int halves = (tiles_per_seq + 1) / 2;
+  const int xcd = blockIdx.x % kXcds, li = blockIdx.x / kXcds;
+  const int pair = xcd * ppx + li / halves, pidx = li % halves;
+  if (li >= ppx * halves || pair >= pairs) return;
+  const int h = pair % Hq, s = pair / Hq;
+  const int t0 = cu_seqlens[s], n = cu_seqlens[s + 1] - t0;
+
+  const int tid = threadIdx.x, lane = tid & 63, ql = lane & 31, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = h / (Hq / Hkv);
+  const int64_t q_stride = (int64_t)Hq * D, kv_stride = (int64_t)Hkv * D;
+
+  // ---- global -> LDS: wave w fills chunks 2w and 2w+1 (4 rows of 256 B each) of every unit.  Lane L of a chunk
+  // writes LDS slot L%16 of row L/16; it fetches the piece that the swizzle assigns to that slot.
+  const unsigned row_bytes = (unsigned)kv_stride * 2;
+  const unsigned extent = (unsigned)(n - 1) * row_bytes + D * 2;
+  const __amdgpu_buffer_rsrc_t krsrc =
+      __builtin_amdgcn_make_buffer_rsrc((void *)(K + (int64_t)t0 * kv_stride + (int64_t)g * D), 0, extent, 0x00020000);
+  const __amdgpu_buffer_rsrc_t vrsrc =
+      __builtin_amdgcn_make_buffer_rsrc((void *)(V + (int64_t)t0 * kv_stride + (int64_t)g * D), 0, extent, 0x00020000);
+  const int lslot = lane & 15;
+  const unsigned wave_lds = (unsigned)(2 * wave * 1024);
+  unsigned koff[2], voff[2];
+  int lrow[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int r = 4 * (2 * wave + i) + (lane >> 4);
+    lrow[i] = r;
+    koff[i] = (unsigned)r * row_bytes + (unsigned)((lslot ^ (r & 15)) * 16);         // K: piece p of row r at slot p ^ (r % 16)
+    voff[i] = (unsigned)r * row_bytes + (unsigned)((lslot ^ ((r & 3) << 2)) * 16);   // V: 64-byte groups rotated by r % 4
+  }
+  // ---- LDS operand addresses (slot 0 of each ring)
+  unsigned kaddr[8], vaddr[4];
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) kaddr[kk] = (unsigned)(ql * 256 + (((2 * kk + hh) ^ (ql & 15)) << 4));
+  {
+    // ds_read_b64_tr_b16: within 16 lanes, result lane i element j = element i%4 of the 8 bytes addressed by lane
+    // 4j + i/4.  Source lane s16 therefore points at key row (s16/4), channels 4*(s16%4).. of its 16-channel block.
+    const int s16 = lane & 15, dhalf = (lane >> 4) & 1;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+      vaddr[db] = (unsigned)(VOFF + (4 * hh + (s16 >> 2)) * 256 + ((db ^ (s16 >> 2)) * 64) + (2 * dhalf + ((s16 & 3) >> 1)) * 16 +
+                             (s16 & 1) * 8);
+  }
+  lds_char *lds = (lds_char *)smem;
+  auto kread = [&](int slot_off, int kk) -> bf16x8 {
+    return __builtin_bit_cast(bf16x8, *(const u32x4 *)(smem + slot_off + kaddr[kk]));
+  };
+  // A operand of O^T += V^T P^T for channel block db and 16-key slab sl of the unit in the given V ring slot
+  auto vread = [&](int slot_off, int sl, int db) -> bf16x8 {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(lds + slot_off + vaddr[db] + sl * 16 * 256));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(lds + slot_off + vaddr[db] + (sl * 16 + 8) * 256));
+    const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+    return __builtin_bit_cast(bf16x8, u32x4{l2.x, l2.y, h2.x, h2.y});
+  };
+
+  for (int rep = 0; rep < 2; ++rep) {
+    const int qt = rep == 0 ? tiles_per_seq - 1 - pidx : pidx;
+    if (rep == 1 && 2 * pidx == tiles_per_seq - 1) break;
+    const int q0 = qt * BMQ;
+    if (q0 >= n) continue;
+    if (rep == 1) __syncthreads();  // the first tile's output staging in LDS has been read
+
+    const int wq0 = q0 + wave * WQ;
+    const int my_q = wq0 + ql;
+    bf16x8 qreg[8];
+    {
+      const int q = min(my_q, n - 1);  // rows past the end compute on a copy and are not stored
+      const uint16_t *qp = Q + (t0 + q) * q_stride + (int64_t)h * D + 8 * hh;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) qreg[kk] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(qp + 16 * kk));
+    }
+    const int kv_end = CAUSAL ? min(n, q0 + BMQ) : n;
+    const int nunits = (kv_end + UK - 1) / UK;
+    const int last_w = CAUSAL ? min(nunits - 1, wq0 / UK) : nunits - 1;  // last unit this wavefront needs
+
+    // rows past the end of the sequence are fetched as copies of the last row (their scores are masked)
+    auto issue = [&](const __amdgpu_buffer_rsrc_t &rsrc, const unsigned (&off)[2], int t, unsigned ring_base, bool is_k) {
+      if (t >= nunits) return;
+      const int k0 = t * UK;
+      const unsigned soff = (unsigned)k0 * row_bytes;
+      const unsigned dst = ring_base + (unsigned)((t % 4) * TB) + wave_lds;
+      if (k0 + UK <= n) {
+        dma16(rsrc, dst, off[0], soff);
+        dma16(rsrc, dst + 1024, off[1], soff);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          const int rr = min(lrow[i], n - 1 - k0);
+          const int sw = is_k ? (lrow[i] & 15) : ((lrow[i] & 3) << 2);
+          dma16(rsrc, dst + i * 1024, (unsigned)rr * row_bytes + (unsigned)((lslot ^ sw) * 16), soff);
+        }
+      }
+    };
+    auto issue_k = [&](int t) { issue(krsrc, koff, t, 0u, true); };
+    auto issue_v = [&](int t) { issue(vrsrc, voff, t, (unsigned)VOFF, false); };
+
+    f32x16 oacc[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) oacc[db][v] = 0.f;
+    float m = -INFINITY, lsum = 0.f;
+
+    // ---- prologue: fill the rings, scores of unit 0, first operands of unit 1
+    issue_k(0);
+    issue_k(1);
+    issue_v(0);
+    issue_k(2);
+    issue_v(1);
+    issue_k(3);
+    issue_v(2);
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) asm volatile("" : "+v"(qreg[kk]));
+    __builtin_amdgcn_s_waitcnt(kVmcnt0);
+    __syncthreads();
+
+    f32x16 s_a, s_b;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s_a[v] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) s_a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kread(0, kk), qreg[kk], s_a, 0, 0, 0);
+    bf16x8 ka[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) ka[kk] = kread(TB, kk);
+
+    // softmax of one unit's scores: probabilities (bf16, B-operand layout of the second product), running
+    // max / sum; the output accumulators are rescaled only when some running maximum grew
+    auto softmax = [&](f32x16 &sc, bf16x8 (&pb)[2], bool need_mask, int k0) {
+      if (need_mask) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int key = k0 + 8 * (v / 4) + 4 * hh + (v % 4);
+          if ((CAUSAL && key > my_q) || key >= n) sc[v] = -INFINITY;
+        }
+      }
+      float mx = fmaxf(sc[0], sc[1]);
+#pragma unroll
+      for (int v = 2; v < 16; ++v) mx = fmaxf(mx, sc[v]);
+      mx = both_max(mx);
+      const float m_new = fmaxf(m, mx);
+      const float ms = (m_new == -INFINITY ? 0.f : m_new) * scale_log2e;
+      const float alpha = __builtin_amdgcn_exp2f(m * scale_log2e - ms);
+      const bool grew = m_new > m;
+      m = m_new;
+      float psum = 0.f;
+      float p[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        p[v] = __builtin_amdgcn_exp2f(fmaf(sc[v], scale_log2e, -ms));
+        psum += p[v];
+      }
+      lsum = lsum * alpha + psum;
+#pragma unroll
+      for (int sl = 0; sl < 2; ++sl) {
+        u32x4 pw;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pw[e] = pack_bf16(p[8 * sl + 2 * e], p[8 * sl + 2 * e + 1]);
+        pb[sl] = __builtin_bit_cast(bf16x8, pw);
+      }
+      if (__any(grew)) {
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
+      }
+    };
+
+    // One fully visible unit u (u % 4 == I) that is followed by a unit every wavefront of the workgroup needs.
+    // Ring slots are compile-time constants.  Loads issued here: K of unit u+4 (into the slot unit u left after
+    // the previous barrier) and V of unit u+3.  At the closing barrier K of unit u+3 and V of unit u+1 must have
+    // landed: everything but the six most recent loads (V u+2, K u+4, V u+3).
+#define LKV_UNIT(I, S_IN, S_OUT)                                                                                   \
+  {                                                                                                                \
+    constexpr int KS1 = ((I + 1) % KR) * TB, KS2 = ((I + 2) % KR) * TB, VS = (I % VR) * TB;                         \
+    {                                                                                                              \
+      const unsigned so_k = (unsigned)((u + I + 4) * UK) * row_bytes, so_v = (unsigned)((u + I + 3) * UK) * row_bytes; \
+      constexpr unsigned DK = (I % KR) * TB, DV = VOFF + ((I + 3) % VR) * TB;                                      \
+      dma16(krsrc, DK + wave_lds, koff[0], so_k);                                                                  \
+      dma16(krsrc, DK + wave_lds + 1024, koff[1], so_k);                                                           \
+      dma16(vrsrc, DV + wave_lds, voff[0], so_v);                                                                  \
+      dma16(vrsrc, DV + wave_lds + 1024, voff[1], so_v);                                                           \
+    }                                                                                                              \
+    bf16x8 kb[4], va[4], vb[4], pb[2];                                                                             \
+    _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) kb[kk] = kread(KS1, 4 + kk);                                   \
+    _Pragma("unroll") for (int db = 0; db < 4; ++db) va[db] = vread(VS, 0, db);                                     \
+    _Pragma("unroll") for (int v = 0; v < 16; ++v) S_OUT[v] = 0.f;                                                  \
+    _Pragma("unroll") for (int kk = 0; kk < 4; ++kk)                                                                \
+        S_OUT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk], qreg[kk], S_OUT, 0, 0, 0);                          \
+    _Pragma("unroll") for (int kk = 0; kk < 4; ++kk)                                                                \
+        S_OUT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb[kk], qreg[4 + kk], S_OUT, 0, 0, 0);                      \
+    softmax(S_IN, pb, false, 0);                                                                                   \
+    _Pragma("unroll") for (int db = 0; db < 4; ++db) vb[db] = vread(VS, 1, db);                                     \
+    _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) ka[kk] = kread(KS2, kk);                                       \
+    _Pragma("unroll") for (int db = 0; db < 4; ++db)                                                                \
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[db], pb[0], oacc[db], 0, 0, 0);                       \
+    _Pragma("unroll") for (int db = 0; db < 4; ++db)                                                                \
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[db], pb[1], oacc[db], 0, 0, 0);                       \
+    __builtin_amdgcn_s_waitcnt(kVmcnt6);                                                                           \
+    __syncthreads();                                                                                               \
+  }
+
+    // units below u_main are fully visible to all four wavefronts and are followed by a unit that all of them
+    // need; inside the unrolled loop every unit that is fetched is a complete one (no row clamping)
+    const int u_main = CAUSAL ? min(q0, n) / UK : (n / UK - 1);
+    const int full_units = n / UK;
+    int u = 0;
+    for (; u + 4 <= u_main && u + 8 <= min(nunits, full_units); u += 4) {
+      LKV_UNIT(0, s_a, s_b)
+      LKV_UNIT(1, s_b, s_a)
+      LKV_UNIT(2, s_a, s_b)
+      LKV_UNIT(3, s_b, s_a)
+    }
+#undef LKV_UNIT
+    // remaining units: masks, wavefronts that run out of visible keys, ring slots computed at run time.  The last
+    // loads are issued in iteration nunits-4; after that iteration's barrier every unit is in LDS and none is
+    // overwritten any more, so the wavefronts finish their remaining units without synchronising.
+    f32x16 s_cur = s_a;
+    const int u_sync_last = max(u, nunits - 4);
+    for (; u < nunits; ++u) {
+      issue_k(u + 4);
+      issue_v(u + 3);
+      if (u <= last_w) {
+        const int kslot_n = ((u + 1) % KR) * TB, vslot = (u % VR) * TB;
+        f32x16 s_nxt;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s_nxt[v] = 0.f;
+        if (u + 1 <= last_w) {
+#pragma unroll
+          for (int kk = 0; kk < 8; ++kk)
+            s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kread(kslot_n, kk), qreg[kk], s_nxt, 0, 0, 0);
+        }
+        const int k0 = u * UK;
+        bf16x8 pb[2];
+        softmax(s_cur, pb, (CAUSAL && k0 + UK - 1 > wq0) || (k0 + UK > n), k0);
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl)
+#pragma unroll
+          for (int db = 0; db < 4; ++db)
+            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vread(vslot, sl, db), pb[sl], oacc[db], 0, 0, 0);
+        s_cur = s_nxt;
+      }
+      if (u <= u_sync_last) {
+        __builtin_amdgcn_s_waitcnt(kVmcnt0);
+        __syncthreads();
+      }
+    }
+    __syncthreads();
+
+    // ---- epilogue: O^T -> row-major through LDS (all units are dead: every wavefront passed the barrier above)
+    char *Os = smem + wave * (WQ * OS_STRIDE * 2);
+    {
+      const float l = both_sum(lsum);
+      const float inv = l > 0.f ? 1.f / l : 0.f;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int d0 = 32 * db + 8 * q4 + 4 * hh;
+          u32x2 w = {pack_bf16(oacc[db][4 * q4] * inv, oacc[db][4 * q4 + 1] * inv),
+                     pack_bf16(oacc[db][4 * q4 + 2] * inv, oacc[db][4 * q4 + 3] * inv)};
+          *(u32x2 *)(Os + (ql * OS_STRIDE + d0) * 2) = w;
+        }
+    }
+    __syncthreads();
+    for (int p = lane; p < WQ * (D / 8); p += 64) {
+      const int row = p / (D / 8), pc = p % (D / 8);
+      if (wq0 + row < n)
+        *(u32x4 *)(O + (t0 + wq0 + row) * q_stride + (int64_t)h * D + pc * 8) =
+            *(const u32x4 *)(Os + (row * OS_STRIDE + pc * 8) * 2);
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------ f32
 // 64 queries per workgroup, four lanes per query (each owns D/4 channels), 32-key tiles in LDS.
 template <int D, bool CAUSAL>
@@ -350,6 +676,28 @@ prefill_f32_kernel(const float *__restrict__ Q, const float *__restrict__ K, con
   }
 }
 
+hipError_t launch_bf16_d128(const lkv_ctx *c, const void *Q, const void *K, const void *V, void *O, const int32_t *cu,
+                            int num_seqs, int max_seqlen, int causal, hipStream_t s) {
+  constexpr int D = 128, BMQ = 128;
+  // the kernel addresses a sequence's K/V rows with 32-bit byte offsets
+  if ((int64_t)max_seqlen * c->cfg.num_kv_heads * D * 2 >= ((int64_t)1 << 32)) return hipErrorInvalidValue;
+  const int tiles = (max_seqlen + BMQ - 1) / BMQ, halves = (tiles + 1) / 2;
+  const int64_t pairs = (int64_t)c->cfg.num_q_heads * num_seqs;
+  const int64_t ppx = (pairs + kXcds - 1) / kXcds;
+  if (ppx * halves * kXcds > INT32_MAX) return hipErrorInvalidValue;
+  const float sl2 = c->scale * kLog2e;
+  dim3 grid((unsigned)(ppx * halves * kXcds));
+  if (causal)
+    hipLaunchKernelGGL((prefill_bf16_d128_kernel<true>), grid, dim3(kThreads), 0, s, (const uint16_t *)Q,
+                       (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, cu, c->cfg.num_q_heads,
+                       c->cfg.num_kv_heads, tiles, (int)pairs, sl2);
+  else
+    hipLaunchKernelGGL((prefill_bf16_d128_kernel<false>), grid, dim3(kThreads), 0, s, (const uint16_t *)Q,
+                       (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, cu, c->cfg.num_q_heads,
+                       c->cfg.num_kv_heads, tiles, (int)pairs, sl2);
+  return hipGetLastError();
+}
+
 template <int D>
 hipError_t launch_bf16(const lkv_ctx *c, const void *Q, const void *K, const void *V, void *O, const int32_t *cu,
                        int num_seqs, int max_seqlen, int causal, hipStream_t s) {
@@ -399,7 +747,7 @@ hipError_t launch_prefill(const lkv_ctx *c, const void *Q, const void *K, const 
     return c->cfg.head_dim == 64 ? launch_f32<64>(c, Q, K, V, O, cu, num_seqs, max_seqlen, causal, s)
                                  : launch_f32<128>(c, Q, K, V, O, cu, num_seqs, max_seqlen, causal, s);
   return c->cfg.head_dim == 64 ? launch_bf16<64>(c, Q, K, V, O, cu, num_seqs, max_seqlen, causal, s)
-                               : launch_bf16<128>(c, Q, K, V, O, cu, num_seqs, max_seqlen, causal, s);
+                               : launch_bf16_d128(c, Q, K, V, O, cu, num_seqs, max_seqlen, causal, s);
 }
 
 }  // namespace lkv

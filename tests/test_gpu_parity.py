@@ -185,6 +185,17 @@ def test_non_causal_prefill(dtype, d):
     sc.close()
 
 
+@pytest.mark.parametrize("causal", [True, False])
+def test_bf16_prefill_unit_and_tile_boundaries(causal):
+    """Prompt lengths around the 32-key unit, the 128-query tile and the unrolled four-unit loop of the d=128
+    kernel, in one ragged batch (GQA, so several q heads share each K/V head)."""
+    shape = wl.KVShape(1, 4, 2, 128, 16, "bf16")
+    lens = (1, 31, 32, 33, 127, 128, 129, 255, 256, 257, 383, 385, 1000, 1111, 640)
+    sc = Scenario(15, shape, lens, sum((n + 15) // 16 for n in lens) + 8)
+    sc.prefill_layer(0, causal=causal)
+    sc.close()
+
+
 def test_f32_head_dim_128_and_gqa():
     shape = wl.KVShape(1, 8, 2, 128, 16, "f32")
     sc = Scenario(14, shape, (100, 33), 32)
