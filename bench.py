@@ -25,7 +25,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
-# HBM bytes per launch of the dominant kernel (prefill_bf16_kernel) from two rocprofv3 --pmc runs of this
+# HBM bytes per launch of the dominant kernel (prefill_bf16_d128_kernel) from two rocprofv3 --pmc runs of this
 # command (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for the pack gather
 # kernel, which moves a known 256 MiB each way: see profiles/bench_workload2_hbm_traffic.md
 TRAFFIC_BYTES = {2: 385.4 * 2**20 + 128.0 * 2**20}
@@ -289,6 +289,11 @@ def main():
     iso["decode_paged_attn_GBps"] = decode_bytes_per_launch[0] / (t_decode * 1e-3) / 1e9
     iso = {k: round(v, 2) for k, v in iso.items()}
     traffic = TRAFFIC_BYTES.get(args.workload)
+    # what a pure bf16 MFMA stream sustains on this machine right now (random operand bits, as in real data; then
+    # constant operands): the published peak assumes the boost clock, which a matrix load does not hold
+    torch.cuda.synchronize()
+    mf_rand = c.probe_mfma_rate(30.0, True, eng.main)
+    mf_const = c.probe_mfma_rate(30.0, False, eng.main)
 
     out = {
         "metric": METRIC, "value": round(decode_gbs, 2), "unit": "GB/s",
@@ -322,10 +327,18 @@ def main():
         "overlap": overlap,
         "kernels_alone": dict(iso, note="each kernel launched back to back with nothing else on the GPU; the "
                                         "components above are measured inside the full step, where streams overlap"),
-        "roofline": {"kernel": "prefill_bf16_kernel (lkv_prefill_attention)", "bound": "mfma",
+        "roofline": {"kernel": "prefill_bf16_d128_kernel (lkv_prefill_attention)", "bound": "mfma",
                      "achieved": round(prefill_tflops, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(prefill_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic,
-                     "launch_ms": round(avg("prefill_attention"), 4), "flops_per_launch": pf_flops},
+                     "launch_ms": round(avg("prefill_attention"), 4), "flops_per_launch": pf_flops,
+                     "mfma_stream_sustained": {
+                         "random_operands_TFLOPs": round(mf_rand[0], 1), "random_operands_clock_MHz": round(mf_rand[1]),
+                         "constant_operands_TFLOPs": round(mf_const[0], 1),
+                         "constant_operands_clock_MHz": round(mf_const[1]),
+                         "frac_of_random_operand_stream": round(prefill_tflops / mf_rand[0], 4),
+                         "note": "lkv_probe_mfma_rate: nothing but v_mfma_f32_32x32x16_bf16 for 30 ms, two wavefronts "
+                                 "per SIMD; the clock under a matrix load depends on the operand bits, so the published "
+                                 "2.5 PFLOP/s (2.4 GHz) is not reachable with real data on this box"}},
         "rooflines_other": {
             "decode": {"bound": "hbm", "achieved": round(decode_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                        "frac": round(decode_gbs / HBM_PEAK_GBS, 4)},

@@ -202,6 +202,15 @@ lkv_status lkv_set_profiling(lkv_ctx *ctx, int32_t on);
  * for the timed launches recorded so far. */
 lkv_status lkv_get_stats(lkv_ctx *ctx, lkv_stats *out, int64_t size);
 
+/* Measurement helper, not a step of the path: runs a stream of bf16 MFMAs (v_mfma_f32_32x32x16_bf16, two
+ * wavefronts per SIMD on every CU, nothing else in the loop) for about `millis` milliseconds (clamped to 200) on
+ * the context's device and `stream`, and reports the rate it sustained (*tflops, host) and the average shader
+ * clock during the run (*clock_mhz, host).  random_operands != 0 uses operands with random signs and mantissas,
+ * 0 uses the constant 1.0: under a matrix load the clock, and with it the reachable rate, depends on how many
+ * operand bits toggle.  Blocks the host; allocates and frees a few bytes of device memory. */
+lkv_status lkv_probe_mfma_rate(lkv_ctx *ctx, double millis, int32_t random_operands, double *tflops,
+                               double *clock_mhz, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -33,6 +33,7 @@ EXPORTS = (
     "lkv_write_kv", "lkv_prefill_attention", "lkv_pack_layer_blocks", "lkv_unpack_layer_blocks",
     "lkv_paged_decode_attention",
     "lkv_stream_wait_event", "lkv_event_synchronize", "lkv_set_profiling", "lkv_get_stats",
+    "lkv_probe_mfma_rate",
 )
 
 
@@ -101,6 +102,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "lkv_event_synchronize": (i32, [vp, i32, i32]),
         "lkv_set_profiling": (i32, [vp, i32]),
         "lkv_get_stats": (i32, [vp, P(LkvStats), i64]),
+        "lkv_probe_mfma_rate": (i32, [vp, ctypes.c_double, i32, P(ctypes.c_double), P(ctypes.c_double), vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -267,6 +269,13 @@ class LKV:
 
     def set_profiling(self, on: bool) -> None:
         self._check(self.lib.lkv_set_profiling(self.h, int(bool(on))))
+
+    def probe_mfma_rate(self, millis: float = 20.0, random_operands: bool = True, stream=None):
+        """(TFLOP/s, shader clock in MHz) a pure bf16 MFMA stream sustains on this GPU right now."""
+        tf, mhz = ctypes.c_double(0.0), ctypes.c_double(0.0)
+        self._check(self.lib.lkv_probe_mfma_rate(self.h, float(millis), int(bool(random_operands)), ctypes.byref(tf),
+                                                 ctypes.byref(mhz), _stream(stream)))
+        return tf.value, mhz.value
 
     def get_stats(self) -> dict:
         s = LkvStats()

@@ -12,7 +12,8 @@ namespace {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kThreads = 256;
-constexpr int kUnroll = 4;
+constexpr int kUnroll = 4;         // 16-byte loads in flight per thread: reads from scattered blocks
+constexpr int kUnrollScatter = 2;  // measured: writes into scattered blocks run ~8% faster with two
 
 struct Div {  // x / d and x % d; shift >= 0 marks a power of two
   uint32_t d;
@@ -37,15 +38,16 @@ __device__ __forceinline__ void divmod(int64_t x, Div dv, int64_t &q, uint32_t &
 }
 
 // One 16-byte piece per (token, K|V, kv head, piece-in-row).
+template <int UNROLL>
 __global__ void __launch_bounds__(kThreads)
 write_kv_kernel(const char *__restrict__ K, const char *__restrict__ V, const int64_t *__restrict__ slots,
                 char *__restrict__ pool, int64_t total_pieces, Div pieces_per_row, Div heads, Div block_size,
                 int64_t row_bytes, int64_t block_bytes) {
-  int64_t base = ((int64_t)blockIdx.x * kUnroll) * kThreads + threadIdx.x;
-  u32x4 val[kUnroll];
-  int64_t dst[kUnroll];
+  int64_t base = ((int64_t)blockIdx.x * UNROLL) * kThreads + threadIdx.x;
+  u32x4 val[UNROLL];
+  int64_t dst[UNROLL];
 #pragma unroll
-  for (int u = 0; u < kUnroll; ++u) {
+  for (int u = 0; u < UNROLL; ++u) {
     int64_t i = base + (int64_t)u * kThreads;
     dst[u] = -1;
     if (i >= total_pieces) continue;
@@ -64,20 +66,20 @@ write_kv_kernel(const char *__restrict__ K, const char *__restrict__ V, const in
              (int64_t)piece * 16;
   }
 #pragma unroll
-  for (int u = 0; u < kUnroll; ++u)
+  for (int u = 0; u < UNROLL; ++u)
     if (dst[u] >= 0) *(u32x4 *)(pool + dst[u]) = val[u];
 }
 
 // GATHER: staging[i*beta + o] = pool[ids[i]*beta + o];  !GATHER: the inverse.
-template <bool GATHER>
+template <bool GATHER, int UNROLL>
 __global__ void __launch_bounds__(kThreads)
 move_blocks_kernel(char *__restrict__ pool, char *__restrict__ staging, const int32_t *__restrict__ ids,
                    int64_t total_pieces, Div pieces_per_block, int64_t block_bytes) {
-  int64_t base = ((int64_t)blockIdx.x * kUnroll) * kThreads + threadIdx.x;
-  u32x4 val[kUnroll];
-  int64_t dst[kUnroll];
+  int64_t base = ((int64_t)blockIdx.x * UNROLL) * kThreads + threadIdx.x;
+  u32x4 val[UNROLL];
+  int64_t dst[UNROLL];
 #pragma unroll
-  for (int u = 0; u < kUnroll; ++u) {
+  for (int u = 0; u < UNROLL; ++u) {
     int64_t i = base + (int64_t)u * kThreads;
     dst[u] = -1;
     if (i >= total_pieces) continue;
@@ -95,11 +97,11 @@ move_blocks_kernel(char *__restrict__ pool, char *__restrict__ staging, const in
     }
   }
 #pragma unroll
-  for (int u = 0; u < kUnroll; ++u)
+  for (int u = 0; u < UNROLL; ++u)
     if (dst[u] >= 0) __builtin_nontemporal_store(val[u], (u32x4 *)((GATHER ? staging : pool) + dst[u]));
 }
 
-unsigned grid_for(int64_t pieces) { return (unsigned)((pieces + (int64_t)kThreads * kUnroll - 1) / ((int64_t)kThreads * kUnroll)); }
+unsigned grid_for(int64_t pieces, int unroll) { return (unsigned)((pieces + (int64_t)kThreads * unroll - 1) / ((int64_t)kThreads * unroll)); }
 
 }  // namespace
 
@@ -110,7 +112,7 @@ hipError_t launch_write_kv(const lkv_ctx *c, const void *K, const void *V, const
   int64_t pieces_per_row = c->row_bytes / 16;
   int64_t total = num_tokens * 2 * c->cfg.num_kv_heads * pieces_per_row;
   if (total == 0) return hipSuccess;
-  hipLaunchKernelGGL(write_kv_kernel, dim3(grid_for(total)), dim3(kThreads), 0, s, (const char *)K, (const char *)V,
+  hipLaunchKernelGGL(write_kv_kernel<kUnrollScatter>, dim3(grid_for(total, kUnrollScatter)), dim3(kThreads), 0, s, (const char *)K, (const char *)V,
                      slots, c->pool, total, make_div(pieces_per_row), make_div(c->cfg.num_kv_heads),
                      make_div(c->cfg.block_size), c->row_bytes, c->block_bytes);
   return hipGetLastError();
@@ -119,7 +121,7 @@ hipError_t launch_write_kv(const lkv_ctx *c, const void *K, const void *V, const
 hipError_t launch_gather_blocks(const lkv_ctx *c, const int32_t *ids_dev, int64_t n, char *dst, hipStream_t s) {
   int64_t total = n * (c->block_bytes / 16);
   if (total == 0) return hipSuccess;
-  hipLaunchKernelGGL(move_blocks_kernel<true>, dim3(grid_for(total)), dim3(kThreads), 0, s, c->pool, dst, ids_dev,
+  hipLaunchKernelGGL((move_blocks_kernel<true, kUnroll>), dim3(grid_for(total, kUnroll)), dim3(kThreads), 0, s, c->pool, dst, ids_dev,
                      total, make_div(c->block_bytes / 16), c->block_bytes);
   return hipGetLastError();
 }
@@ -127,7 +129,7 @@ hipError_t launch_gather_blocks(const lkv_ctx *c, const int32_t *ids_dev, int64_
 hipError_t launch_scatter_blocks(const lkv_ctx *c, const int32_t *ids_dev, int64_t n, const char *src, hipStream_t s) {
   int64_t total = n * (c->block_bytes / 16);
   if (total == 0) return hipSuccess;
-  hipLaunchKernelGGL(move_blocks_kernel<false>, dim3(grid_for(total)), dim3(kThreads), 0, s, c->pool,
+  hipLaunchKernelGGL((move_blocks_kernel<false, kUnrollScatter>), dim3(grid_for(total, kUnrollScatter)), dim3(kThreads), 0, s, c->pool,
                      const_cast<char *>(src), ids_dev, total, make_div(c->block_bytes / 16), c->block_bytes);
   return hipGetLastError();
 }

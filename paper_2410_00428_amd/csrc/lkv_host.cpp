@@ -553,6 +553,15 @@ lkv_status lkv_set_profiling(lkv_ctx *c, int32_t on) {
   return LKV_OK;
 }
 
+lkv_status lkv_probe_mfma_rate(lkv_ctx *c, double millis, int32_t random_operands, double *tflops, double *clock_mhz,
+                               void *stream) {
+  if (!c || !tflops || !clock_mhz) return LKV_ERR_INVALID_ARG;
+  if (c->logical_only) return fail(c, LKV_ERR_DEVICE, "lkv_probe_mfma_rate: this context has no device resources");
+  LKV_HIP(c, hipSetDevice(c->device));
+  LKV_HIP(c, lkv::probe_mfma_rate(millis, random_operands, tflops, clock_mhz, (hipStream_t)stream));
+  return LKV_OK;
+}
+
 lkv_status lkv_get_stats(lkv_ctx *c, lkv_stats *out, int64_t size) {
   if (!c || !out || size < 0) return LKV_ERR_INVALID_ARG;
   for (auto &t : c->timed) {

@@ -100,4 +100,7 @@ hipError_t launch_prefill(const lkv_ctx *c, const void *Q, const void *K, const 
                           hipStream_t s);
 bool prefill_supported(const lkv_ctx *c);
 
+// Sustained bf16 MFMA rate and shader clock of the current device (measurement helper).
+hipError_t probe_mfma_rate(double millis, int random_operands, double *tflops, double *clock_mhz, hipStream_t s);
+
 }  // namespace lkv

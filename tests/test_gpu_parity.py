@@ -325,3 +325,18 @@ def test_offload_on_side_stream_overlapping_next_layers_compute():
         sc.decode_step(layer, stream=main)
     sc.check_pool("after overlapped offload/reload")
     sc.close()
+
+
+def test_mfma_probe_reports_a_plausible_rate_and_clock():
+    """Measurement helper: the sustained MFMA rate equals 4 SIMDs x 1024 flop/clock x CUs x measured clock
+    (the stream keeps the pipes full), and constant operands never run slower than random ones."""
+    c = lkv.LKV(1, 4, 4, 128, 16, 8, "bf16")
+    tf_r, mhz_r = c.probe_mfma_rate(5.0, True)
+    tf_c, mhz_c = c.probe_mfma_rate(5.0, False)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    for tf, mhz in ((tf_r, mhz_r), (tf_c, mhz_c)):
+        assert 500.0 < mhz < 3000.0
+        pipe_rate = cus * 4 * 1024 * mhz * 1e6 / 1e12
+        assert 0.85 * pipe_rate < tf < 1.02 * pipe_rate, (tf, mhz, pipe_rate)
+    assert tf_c > 0.9 * tf_r
+    c.destroy()
