@@ -105,6 +105,12 @@ typedef struct {
    * (read + write) in those launches */
   int64_t pack_kernel_ns, pack_kernel_bytes;
   int64_t unpack_kernel_ns, unpack_kernel_bytes;
+  /* likewise while profiling is on: GPU time between an event recorded right before and one right after the
+   * kernel launches of lkv_write_kv, lkv_prefill_attention and lkv_paged_decode_attention (the latter includes
+   * the combine kernel when the context is split), and how many calls were timed */
+  int64_t write_kernel_ns, write_kernel_launches;
+  int64_t prefill_kernel_ns, prefill_kernel_launches;
+  int64_t decode_kernel_ns, decode_kernel_launches;
 } lkv_stats;
 
 /* ------------------------------------------------------------------ life cycle */
@@ -195,8 +201,8 @@ lkv_status lkv_paged_decode_attention(lkv_ctx *ctx, int32_t layer, const void *Q
 lkv_status lkv_stream_wait_event(lkv_ctx *ctx, int32_t layer, int32_t ev, void *stream);
 /* Blocks the host until that event has happened. */
 lkv_status lkv_event_synchronize(lkv_ctx *ctx, int32_t layer, int32_t ev);
-/* Turns per-launch HIP-event timing of the pack / unpack kernels on or off (off by default; each
- * timed launch costs two extra event records).  Results accumulate in lkv_stats. */
+/* Turns per-launch HIP-event timing of the library's kernels on or off (off by default; each timed launch
+ * costs two extra event records).  Results accumulate in lkv_stats. */
 lkv_status lkv_set_profiling(lkv_ctx *ctx, int32_t on);
 /* Copies min(size, sizeof(lkv_stats)) bytes of counters to out (host).  With profiling on this waits
  * for the timed launches recorded so far. */

@@ -48,7 +48,8 @@ class LkvStats(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int64) for n in
                 ("write_kv_calls", "write_kv_bytes", "prefill_calls", "decode_calls", "pack_calls", "pack_bytes",
                  "unpack_calls", "unpack_bytes", "pack_kernel_ns", "pack_kernel_bytes", "unpack_kernel_ns",
-                 "unpack_kernel_bytes")]
+                 "unpack_kernel_bytes", "write_kernel_ns", "write_kernel_launches", "prefill_kernel_ns",
+                 "prefill_kernel_launches", "decode_kernel_ns", "decode_kernel_launches")]
 
 
 class LkvError(RuntimeError):

@@ -129,7 +129,7 @@ lkv_status timed_begin(lkv_ctx *c, hipStream_t s, hipEvent_t *a) {
   return LKV_OK;
 }
 
-lkv_status timed_end(lkv_ctx *c, hipStream_t s, hipEvent_t a, int64_t bytes, bool unpack) {
+lkv_status timed_end(lkv_ctx *c, hipStream_t s, hipEvent_t a, int64_t bytes, int kind) {
   if (!a) return LKV_OK;
   hipEvent_t b;
   if (c->spare_events.empty()) {
@@ -139,7 +139,7 @@ lkv_status timed_end(lkv_ctx *c, hipStream_t s, hipEvent_t a, int64_t bytes, boo
     c->spare_events.pop_back();
   }
   LKV_HIP(c, hipEventRecord(b, s));
-  c->timed.push_back({a, b, bytes, unpack});
+  c->timed.push_back({a, b, bytes, kind});
   return LKV_OK;
 }
 
@@ -405,7 +405,10 @@ lkv_status lkv_write_kv(lkv_ctx *c, int32_t layer, const void *K, const void *V,
   if (num_tokens > 0) {
     if (!K || !V || !slot_mapping) return fail(c, LKV_ERR_INVALID_ARG, "lkv_write_kv: NULL pointer");
     if (((uintptr_t)K | (uintptr_t)V) & 15) return fail(c, LKV_ERR_INVALID_ARG, "lkv_write_kv: K and V must be 16-byte aligned");
+    hipEvent_t t0;
+    if (lkv_status st = timed_begin(c, s, &t0)) return st;
     LKV_HIP(c, lkv::launch_write_kv(c, K, V, slot_mapping, num_tokens, s));
+    if (lkv_status st = timed_end(c, s, t0, 2 * num_tokens * c->token_bytes, lkv_ctx::kTimedWrite)) return st;
   }
   c->stats.write_kv_calls += 1;
   c->stats.write_kv_bytes += num_tokens * c->token_bytes;
@@ -426,7 +429,10 @@ lkv_status lkv_prefill_attention(lkv_ctx *c, int32_t layer, const void *Q, const
   if (!Q || !K || !V || !O || !cu_seqlens) return fail(c, LKV_ERR_INVALID_ARG, "lkv_prefill_attention: NULL pointer");
   if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15)
     return fail(c, LKV_ERR_INVALID_ARG, "lkv_prefill_attention: tensors must be 16-byte aligned");
+  hipEvent_t t0;
+  if (lkv_status st = timed_begin(c, (hipStream_t)stream, &t0)) return st;
   LKV_HIP(c, lkv::launch_prefill(c, Q, K, V, O, cu_seqlens, num_seqs, max_seqlen, causal, (hipStream_t)stream));
+  if (lkv_status st = timed_end(c, (hipStream_t)stream, t0, 0, lkv_ctx::kTimedPrefill)) return st;
   c->stats.prefill_calls += 1;
   return LKV_OK;
 }
@@ -449,7 +455,7 @@ lkv_status lkv_pack_layer_blocks(lkv_ctx *c, int32_t layer, const int32_t *block
     hipEvent_t t0;
     if (lkv_status st = timed_begin(c, s, &t0)) return st;
     LKV_HIP(c, lkv::launch_gather_blocks(c, sg.ids_dev + (size_t)slot * c->staging_blocks, m, sg.buf, s));
-    if (lkv_status st = timed_end(c, s, t0, 2 * m * c->block_bytes, false)) return st;
+    if (lkv_status st = timed_end(c, s, t0, 2 * m * c->block_bytes, lkv_ctx::kTimedPack)) return st;
     LKV_HIP(c, hipEventRecord(sg.slot_done[slot], s));
     if (first + m == n)
       if (lkv_status st = record_event(c, layer, LKV_EV_PACKED, s)) return st;
@@ -488,7 +494,7 @@ lkv_status lkv_unpack_layer_blocks(lkv_ctx *c, int32_t layer, const int32_t *blo
     hipEvent_t t0;
     if (lkv_status st = timed_begin(c, s, &t0)) return st;
     LKV_HIP(c, lkv::launch_scatter_blocks(c, sg.ids_dev + (size_t)slot * c->staging_blocks, m, sg.buf, s));
-    if (lkv_status st = timed_end(c, s, t0, 2 * m * c->block_bytes, true)) return st;
+    if (lkv_status st = timed_end(c, s, t0, 2 * m * c->block_bytes, lkv_ctx::kTimedUnpack)) return st;
     LKV_HIP(c, hipEventRecord(sg.slot_done[slot], s));
     LKV_HIP(c, hipEventRecord(sg.buf_free, s));
     sg.buf_used = true;
@@ -525,7 +531,10 @@ lkv_status lkv_paged_decode_attention(lkv_ctx *c, int32_t layer, const void *Q, 
     LKV_HIP(c, hipMalloc((void **)&c->ws, (size_t)need));
     c->ws_bytes = need;
   }
+  hipEvent_t t0;
+  if (lkv_status st = timed_begin(c, s, &t0)) return st;
   LKV_HIP(c, lkv::launch_paged_decode(c, Q, O, block_table, max_blocks_per_seq, context_lens, num_seqs, c->ws, s));
+  if (lkv_status st = timed_end(c, s, t0, 0, lkv_ctx::kTimedDecode)) return st;
   c->stats.decode_calls += 1;
   return LKV_OK;
 }
@@ -569,12 +578,27 @@ lkv_status lkv_get_stats(lkv_ctx *c, lkv_stats *out, int64_t size) {
     float ms = 0.f;
     LKV_HIP(c, hipEventElapsedTime(&ms, t.a, t.b));
     const int64_t ns = (int64_t)((double)ms * 1e6);
-    if (t.unpack) {
-      c->stats.unpack_kernel_ns += ns;
-      c->stats.unpack_kernel_bytes += t.bytes;
-    } else {
-      c->stats.pack_kernel_ns += ns;
-      c->stats.pack_kernel_bytes += t.bytes;
+    switch (t.kind) {
+      case lkv_ctx::kTimedUnpack:
+        c->stats.unpack_kernel_ns += ns;
+        c->stats.unpack_kernel_bytes += t.bytes;
+        break;
+      case lkv_ctx::kTimedPack:
+        c->stats.pack_kernel_ns += ns;
+        c->stats.pack_kernel_bytes += t.bytes;
+        break;
+      case lkv_ctx::kTimedWrite:
+        c->stats.write_kernel_ns += ns;
+        c->stats.write_kernel_launches += 1;
+        break;
+      case lkv_ctx::kTimedPrefill:
+        c->stats.prefill_kernel_ns += ns;
+        c->stats.prefill_kernel_launches += 1;
+        break;
+      default:
+        c->stats.decode_kernel_ns += ns;
+        c->stats.decode_kernel_launches += 1;
+        break;
     }
     c->spare_events.push_back(t.a);
     c->spare_events.push_back(t.b);

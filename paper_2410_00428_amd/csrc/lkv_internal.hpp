@@ -68,11 +68,12 @@ struct lkv_ctx {
   std::vector<int32_t> free_list;  // stack, back() is handed out next
   std::unordered_map<lkv::LayerKey, lkv::LayerState, lkv::LayerKeyHash> layers;
   lkv_stats stats{};
-  // kernel profiling: (start, stop, bytes, is_unpack) of launches not yet folded into stats
+  // kernel profiling: (start, stop, bytes, which kernel) of launches not yet folded into stats
+  enum TimedKind { kTimedPack, kTimedUnpack, kTimedWrite, kTimedPrefill, kTimedDecode };
   struct Timed {
     hipEvent_t a, b;
     int64_t bytes;
-    bool unpack;
+    int kind;
   };
   bool profiling = false;
   std::vector<Timed> timed;
