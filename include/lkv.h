@@ -187,7 +187,9 @@ lkv_status lkv_unpack_layer_blocks(lkv_ctx *ctx, int32_t layer, const int32_t *b
 
 /* Decode attention through this layer's block table (Sections 2.1.2, 2.2, 3.2.2).  Q, O:
  * device, [num_seqs][num_q_heads][head_dim]; block_table: device, int32[num_seqs][max_blocks_per_seq]
- * (entries past ceil(context_len/bs) are ignored); context_lens: device, int32[num_seqs];
+ * (entries past ceil(context_len/bs) are ignored; every entry before that must be a block id of the pool: the
+ * kernels clamp an entry outside [0, num_pool_blocks) into the pool, which gives a wrong row but touches no memory
+ * outside the pool); context_lens: device, int32[num_seqs];
  * sequence s attends to positions 0..context_lens[s]-1; a zero context gives a zero row.
  * Waits (on `stream`) for LKV_EV_RELOADED of the layer.  Long contexts are split into
  * partitions whose partial results are merged by a second kernel; the split-K workspace is

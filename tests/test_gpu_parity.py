@@ -216,6 +216,34 @@ def test_decode_split_k_is_independent_of_partition_size(partition):
     sc.close()
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,max_len", [(16, 8, 1, 1500), (70, 4, 4, 300), (200, 4, 4, 150), (300, 2, 1, 200)])
+def test_decode_ragged_batches_longest_first_work_list(B, Hq, Hkv, max_len):
+    """Split contexts in a ragged batch: the bf16 d=128 kernel derives its (sequence, partition) work list from
+    context_lens inside every workgroup (one register per lane up to 64 sequences, a scan up to 256).  Lengths
+    include exact multiples of the partition, lengths below it, and zero contexts."""
+    shape = wl.KVShape(1, Hq, Hkv, 128, 16, "bf16")
+    rng = np.random.default_rng(1000 + B)
+    lens = [int(x) for x in rng.integers(1, max_len, size=B)]
+    lens[0], lens[1], lens[B // 2], lens[-1] = 64, 128, 192, max_len  # multiples of the 64-token partition
+    sc = Scenario(17, shape, lens, sum((n + 16) // 16 + 1 for n in lens) + 8, decode_partition=64)
+    sc.prefill_layer(0, check_attn=False)
+    sc.decode_step(0)
+    # attend-only variant with some contexts cut to zero or to a partition boundary
+    q, _, _ = wl.decode_qkv(17, 0, 3, B, shape, 1.0)
+    bt = sc.c.padded_block_table(range(B), 0)
+    ctx = np.asarray([n + 1 for n in lens], dtype=np.int32)
+    ctx[2], ctx[1], ctx[B - 2] = 0, 64, 0   # sequence 1 holds 129 tokens: cutting it to 64 stays inside its table
+    assert all(ctx[s] <= lens[s] + 1 for s in range(B))  # a context must never reach past the sequence's blocks
+    Od = H.empty_like_storage(q.shape, "bf16")
+    Od.fill_(0x7FC0)
+    sc.c.paged_decode_attention(0, H.to_dev(q), Od, H.to_dev(bt), bt.shape[1], H.to_dev(ctx), B)
+    got = H.to_host(Od, "bf16")
+    ref = sc.o.paged_decode_attention(q, bt, ctx, threads=ORC_THREADS)
+    assert (got[2] == 0).all() and (got[B - 2] == 0).all()
+    H.check_attention(got, ref, "bf16", 1.0, "ragged decode, attend only")
+    sc.close()
+
+
 def test_decode_zero_context_and_poisoned_unused_slots():
     """context 0 gives a zero row; NaN in unused slots (tail of the last block, stale blocks) must not leak."""
     shape = wl.KVShape(1, 4, 2, 128, 16, "bf16")
