@@ -1,0 +1,223 @@
+"""Host-side policy (Sections 3.1 and 3.2.1 of the paper): the oracle against what the equations and the
+paper's worked example fix, then the library (C ABI, no GPU needed) against the oracle."""
+import itertools
+import math
+import random
+from fractions import Fraction as F
+
+import numpy as np
+import pytest
+
+from oracle import policy_oracle as po
+from paper_2410_00428_amd import binding as lkv
+
+GOLDEN_L8 = [int(t) for line in open(__file__.rsplit("/", 1)[0] + "/golden/retained_layers_L8_x4.txt")
+             if line.startswith("retained ") for t in line.split()[1:]]
+
+
+# ----------------------------------------------------------------------------- oracle pins
+def test_eq3_worked_example_and_shape():
+    # alpha 1, 1000 tokens, 7e9 parameters, hidden 4096, 1e14 FLOP/s: 1000 * (1.4e10 + 8.192e6) / 1e14
+    assert po.prefill_time(1, 1000, 7 * 10**9, 4096, 10**14) == F(1000 * (14 * 10**9 + 8192000), 10**14)
+    # T(s)/s is affine in s with slope 2 alpha n_hidden / FLOPS: the quadratic (attention) term
+    a, h, fl = F(3, 2), 5120, 10**15
+    for s in (7, 128, 4096):
+        slope = po.prefill_time(a, 2 * s, 10**9, h, fl) / (2 * s) - po.prefill_time(a, s, 10**9, h, fl) / s
+        assert slope == a * 2 * s * h / fl
+    assert po.prefill_time(1, 0, 10**9, 4096, 10**12) == 0
+
+
+def test_eq4_counts_the_kv_bytes_of_the_offloaded_layers():
+    # LLaMA-2-7B shape, bf16: one token of one layer is 2 * 32 * 128 * 2 = 16384 bytes; 16 layers of 2048 tokens
+    # are 512 MiB; at 64e9 B/s and beta 1 that is 2^29 / 64e9 seconds
+    t = po.offload_time(1, 2048, 32, 16, 128, 32, 2, 64 * 10**9)
+    assert t == F(2048 * 16 * 16384, 64 * 10**9) == F(2**29, 64 * 10**9)
+    assert po.offload_time(1, 2048, 32, 32, 128, 32, 2, 10**9) == 0          # nothing offloaded
+    assert po.offload_time(2, 100, 8, 3, 64, 4, 4, 10**9) == 2 * po.offload_time(1, 100, 8, 3, 64, 4, 4, 10**9)
+    for x in range(8):   # linear in the number of offloaded layers
+        assert po.offload_time(1, 100, 8, x, 64, 4, 4, 10**9) == (8 - x) * po.offload_time(1, 100, 8, 7, 64, 4, 4, 10**9)
+
+
+def closed_form_x(alpha, n_param, n_hidden, flops, beta, L, d, n, f, bw, s):
+    tp = po.prefill_time(alpha, s, n_param, n_hidden, flops)
+    per_layer = po.offload_time(beta, s, 1, 0, d, n, f, bw)
+    if per_layer == 0:
+        return 0
+    return max(0, math.ceil(L - tp / per_layer))
+
+
+def test_min_retained_layers_closed_form_monotonicity_and_ties():
+    rng = random.Random(5)
+    for _ in range(300):
+        L = rng.randint(1, 80)
+        args = (F(rng.randint(1, 300), 100), rng.choice([0, 10**8, 7 * 10**9, 7 * 10**10]), rng.choice([1024, 4096, 8192]),
+                rng.choice([10**13, 10**14, 2 * 10**15]), F(rng.randint(50, 300), 100), L, rng.choice([64, 128]),
+                rng.choice([1, 8, 32, 64]), rng.choice([1, 2, 4]), rng.choice([16, 32, 64]) * 10**9)
+        xs = [po.min_retained_layers(*args, s) for s in (1, 16, 128, 1024, 8192, 65536, 10**6)]
+        for s, x in zip((1, 16, 128, 1024, 8192, 65536, 10**6), xs):
+            assert x == closed_form_x(*args, s)
+            assert 0 <= x <= L
+        assert xs == sorted(xs, reverse=True)      # longer prompts hide more: x never grows with seqlen
+    # a prompt long enough hides everything: x = 0; no compute at all (alpha = 0) hides nothing: x = L
+    assert po.min_retained_layers(1, 7 * 10**9, 4096, 10**14, 1, 32, 128, 32, 2, 32 * 10**9, 10**7) == 0
+    assert po.min_retained_layers(0, 7 * 10**9, 4096, 10**14, 1, 32, 128, 32, 2, 32 * 10**9, 512) == 32
+    # exact tie: T_prefill equals the offload time of exactly 3 layers -> those 3 may go, x = L - 3
+    per_layer = po.offload_time(1, 64, 1, 0, 128, 8, 2, 10**9)
+    alpha = 3 * per_layer / po.prefill_time(1, 64, 10**6, 1024, 10**12)
+    assert po.min_retained_layers(alpha, 10**6, 1024, 10**12, 1, 10, 128, 8, 2, 10**9, 64) == 7
+
+
+def test_retained_layers_even_spread():
+    assert po.retained_layers(8, 4) == GOLDEN_L8 == [1, 3, 5, 7]       # the paper's example, Section 3.2.2
+    for L in range(1, 41):
+        for x in range(L + 1):
+            r = po.retained_layers(L, x)
+            assert len(r) == x and r == sorted(set(r)) and all(0 <= l < L for l in r)
+            if x >= 2:
+                gaps = [b - a for a, b in zip(r, r[1:])]
+                assert max(gaps) - min(gaps) <= 1
+    assert po.retained_layers(5, 5) == [0, 1, 2, 3, 4] and po.retained_layers(5, 0) == []
+
+
+def test_eq1_worked_example_and_identity():
+    # target 0.1 s/token, 50 tokens in 4.0 s (0.08 s/token so far), predicted range starts at 150 tokens:
+    # N_future 100, T_future 8.0, T_allow = 0.1 * 150 - 12.0 = 3.0
+    assert po.allow_prefill_time(F(1, 10), 50, 4, 150) == 3
+    rng = random.Random(9)
+    for _ in range(200):
+        tt, n_past, t_past, lo = F(rng.randint(1, 500), 1000), rng.randint(1, 400), F(rng.randint(0, 90000), 1000), rng.randint(0, 600)
+        nf = po.n_future(n_past, lo)
+        assert nf >= 1 and nf == max(1, lo - n_past)
+        # T_past + T_future = current TPOT * (N_past + N_future): the slack is the TPOT margin times all tokens
+        assert po.allow_prefill_time(tt, n_past, t_past, lo) == (tt - t_past / n_past) * (n_past + nf)
+    assert po.allow_prefill_time(F(1, 10), 40, 4, 100) == 0               # exactly on target: nothing to give
+    assert po.allow_prefill_time(F(1, 10), 40, 5, 100) < 0                # behind target
+    assert po.allow_prefill_time(F(1, 10), 0, F(3, 10), 20) == -F(3, 10)  # nothing produced yet: only the waiting counts
+
+
+def test_algorithm1_against_brute_force():
+    rng = random.Random(11)
+    for _ in range(300):
+        allow = [F(rng.randint(-50, 400), 10) for _ in range(rng.randint(0, 5))]
+        queue = [F(rng.randint(1, 120), 10) for _ in range(rng.randint(0, 7))]
+        got = po.max_prefills(allow, queue)
+        if not allow:
+            assert got == len(queue)
+            continue
+        budget = min(allow)
+        ok = [n for n in range(len(queue) + 1) if all(sum(queue[:m]) < budget for m in range(1, n + 1))]
+        assert got == max(ok)
+    assert po.max_prefills([5], [2, 3, 1]) == 1      # 2 + 3 = 5 is not < 5: strict
+    assert po.max_prefills([0], [1]) == 0 and po.max_prefills([-1], []) == 0
+
+
+def test_eq5_telescopes_and_threshold():
+    rng = random.Random(13)
+    for _ in range(100):
+        T = rng.randint(0, 12)
+        rel = [rng.randint(0, 40) for _ in range(T)]
+        alc = [rng.randint(0, 40) for _ in range(T)]
+        a0 = rng.randint(0, 200)
+        f = po.forecast_avail(a0, rel, alc)
+        assert len(f) == T
+        for t in range(T):
+            assert f[t] == a0 + sum(rel[:t + 1]) - sum(alc[:t + 1])
+        thr = rng.randint(0, 150)
+        first = po.first_stage_below(a0, rel, alc, thr)
+        below = [t + 1 for t in range(T) if f[t] < thr]
+        assert first == (below[0] if below else -1)
+
+
+def test_pressure_rule_examples_and_properties():
+    assert po.pressure_offload(15, [4, 4, 2], [10, 10, 5]) == [2, 0, 0]     # half of the most recent request suffices
+    assert po.pressure_offload(45, [4, 4, 2], [10, 10, 5]) == [2, 2, 1]     # halves of all three
+    assert po.pressure_offload(60, [4, 4, 2], [10, 10, 5]) == [4, 2, 1]     # halves were not enough: rest of the first
+    assert po.pressure_offload(10**6, [4, 4, 2], [10, 10, 5]) == [4, 4, 2]  # everything, still short
+    assert po.pressure_offload(0, [4, 4], [10, 10]) == [0, 0]
+    assert po.pressure_offload(3, [1], [8]) == [1]                          # a single retained layer can go
+    rng = random.Random(17)
+    for _ in range(300):
+        R = rng.randint(0, 6)
+        x = [rng.randint(0, 9) for _ in range(R)]
+        b = [rng.randint(1, 20) for _ in range(R)]
+        d = rng.randint(-5, 300)
+        g = po.pressure_offload(d, x, b)
+        assert all(0 <= gi <= xi for gi, xi in zip(g, x))
+        freed = sum(gi * bi for gi, bi in zip(g, b))
+        if d > 0 and freed < d:
+            assert g == x                                                   # short even after giving all
+        # nothing is taken from a request while a more recent one still has its first half
+        halves = [(xi + 1) // 2 for xi in x]
+        for r in range(1, R):
+            if g[r] > 0:
+                assert all(g[q] >= halves[q] for q in range(r))
+        # the second pass only starts when all first halves together were not enough
+        if any(gi > hi for gi, hi in zip(g, halves)):
+            assert sum(hi * bi for hi, bi in zip(halves, b)) < d
+
+
+# ----------------------------------------------------------------------------- library against the oracle
+def model(rng):
+    return dict(alpha=rng.uniform(0.5, 3.0), n_param=rng.choice([0.0, 1e8, 7e9, 7e10]), n_hidden=rng.choice([1024.0, 4096.0, 8192.0]),
+                device_flops=rng.choice([1e13, 1e14, 2.5e15]), beta=rng.uniform(0.5, 3.0), num_layers=rng.randint(1, 80),
+                head_dim=rng.choice([64, 128]), num_heads=rng.choice([1, 8, 32, 64]), bytes_per_elem=rng.choice([1.0, 2.0, 4.0]),
+                link_bytes_per_s=rng.choice([16e9, 32e9, 57e9]))
+
+
+def test_library_cost_model_matches_oracle():
+    rng = random.Random(21)
+    for _ in range(200):
+        m = model(rng)
+        cm = lkv.CostModel(**m)
+        fm = {k: F(v) for k, v in m.items()}
+        for s in (1, 77, 2048, 16384, 10**6):
+            tp = po.prefill_time(fm["alpha"], s, fm["n_param"], fm["n_hidden"], fm["device_flops"])
+            assert lkv.prefill_time(cm, s) == pytest.approx(float(tp), rel=1e-12)
+            for x in (0, m["num_layers"] // 2, m["num_layers"]):
+                to = po.offload_time(fm["beta"], s, m["num_layers"], x, m["head_dim"], m["num_heads"], fm["bytes_per_elem"],
+                                     fm["link_bytes_per_s"])
+                assert lkv.offload_time(cm, s, x) == pytest.approx(float(to), rel=1e-12, abs=0)
+            want = po.min_retained_layers(fm["alpha"], fm["n_param"], fm["n_hidden"], fm["device_flops"], fm["beta"],
+                                          m["num_layers"], m["head_dim"], m["num_heads"], fm["bytes_per_elem"],
+                                          fm["link_bytes_per_s"], s)
+            got_x, mask = lkv.plan_offload(cm, s)
+            assert got_x == want                     # random doubles: no exact ties
+            assert [l for l in range(m["num_layers"]) if mask[l]] == po.retained_layers(m["num_layers"], want)
+    # the tie of the oracle test, in numbers that doubles hold exactly: x = 7
+    cm = lkv.CostModel(alpha=3 * (64 * 2 * 128 * 8 * 2 / 2.0**30) / (64 * (2 * 2.0**20 + 2 * 64 * 1024) / 2.0**40), n_param=2.0**20,
+                       n_hidden=1024.0, device_flops=2.0**40, beta=1.0, num_layers=10, head_dim=128, num_heads=8,
+                       bytes_per_elem=2.0, link_bytes_per_s=2.0**30)
+    assert lkv.plan_offload(cm, 64)[0] == 7
+    with pytest.raises(lkv.LkvError):
+        lkv.plan_offload(lkv.CostModel(**dict(model(rng), num_layers=0)), 10)
+
+
+def test_library_scheduler_matches_oracle():
+    rng = random.Random(23)
+    for _ in range(300):
+        reqs = [dict(t_tpot=rng.randint(1, 500) / 1024, n_past=rng.randint(0, 400), t_past=rng.randint(0, 90000) / 1024,
+                     predicted_lower_bound=rng.randint(0, 600)) for _ in range(rng.randint(0, 5))]
+        queue = [rng.randint(1, 120) / 16 for _ in range(rng.randint(0, 7))]
+        allow_o = [po.allow_prefill_time(F(r["t_tpot"]), r["n_past"], F(r["t_past"]), r["predicted_lower_bound"]) for r in reqs]
+        allow_l = [lkv.allow_prefill_time(**r) for r in reqs]
+        for a, b in zip(allow_l, allow_o):
+            assert a == pytest.approx(float(b), rel=1e-12, abs=1e-12)
+        assert lkv.max_prefills(reqs, queue) == po.max_prefills(allow_o, [F(q) for q in queue])
+    assert lkv.max_prefills([], [1.0, 2.0]) == 2
+    assert lkv.max_prefills([dict(t_tpot=0.125, n_past=40, t_past=4.0, predicted_lower_bound=80)], [0.5, 0.25, 0.25]) == 2  # slack 1.0: 0.5+0.25 < 1
+
+
+def test_library_forecast_and_pressure_match_oracle():
+    rng = random.Random(29)
+    for _ in range(200):
+        T = rng.randint(0, 12)
+        rel = [rng.randint(0, 40) for _ in range(T)]
+        alc = [rng.randint(0, 40) for _ in range(T)]
+        a0, thr = rng.randint(0, 200), rng.randint(0, 150)
+        f, first = lkv.forecast_avail(a0, rel, alc, thr)
+        assert f == po.forecast_avail(a0, rel, alc) and first == po.first_stage_below(a0, rel, alc, thr)
+        R = rng.randint(0, 6)
+        x = [rng.randint(0, 9) for _ in range(R)]
+        b = [rng.randint(1, 20) for _ in range(R)]
+        d = rng.randint(-5, 300)
+        assert lkv.pressure_offload(d, x, b) == po.pressure_offload(d, x, b)
