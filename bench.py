@@ -218,11 +218,12 @@ def main():
     del big, big_host
 
     def prefill_phase(offload):
+        """offload: False, True (the workload's layers) or an explicit {layer: pinned buffer}."""
         eng.reset()
         eng.begin_prompts(w.prompt_lens)
         a, b, d = ev(), ev(), ev()
         a.record(eng.main)
-        eng.prefill_all_layers(Qs, Ks, Vs, O, pinned if offload else {})
+        eng.prefill_all_layers(Qs, Ks, Vs, O, offload if isinstance(offload, dict) else (pinned if offload else {}))
         b.record(eng.main)
         d.record(eng.d2h)
         torch.cuda.synchronize()
@@ -270,6 +271,40 @@ def main():
                    "note": "hidden = 1 - (wall(prefill with offload) - wall(prefill alone)) / wall(offload alone); bound = "
                            "compute issued after the first offload starts / link time: attention-only compute cannot "
                            "hide a PCIe transfer of the same layers"}
+        # The paper's own answer to that (Section 3.2.1): retain x layers, x the smallest number whose offload
+        # time does not exceed the prefill time.  Both models are fitted to THIS run: alpha from the measured
+        # prefill phase (attention only: no weights on this path, n_param = 0), beta from the measured link time.
+        from paper_2410_00428_amd import binding as lkv_b
+        n_tok = sum(w.prompt_lens)
+        cm = lkv_b.CostModel(alpha=1.0, n_param=0.0, n_hidden=float(L * sh.num_q_heads * sh.head_dim),
+                             device_flops=MFMA_BF16_PEAK_TFLOPS * 1e12, beta=1.0, num_layers=L, head_dim=sh.head_dim,
+                             num_heads=sh.num_kv_heads, bytes_per_elem=2.0, link_bytes_per_s=link["d2h"] * 1e9)
+        # the batch is B equal prompts: per-request times are the phase times divided by B
+        s_req = w.prompt_lens[0]
+        cm.alpha = (t_compute * 1e-3 / B) / lkv_b.prefill_time(cm, s_req)
+        cm.beta = (t_link * 1e-3 / B) / lkv_b.offload_time(cm, s_req, L - len(off_layers))
+        x_plan, mask = lkv_b.plan_offload(cm, s_req)
+        planned = [l for l in range(L) if not mask[l]]
+        plan = {"alpha": round(cm.alpha, 3), "beta": round(cm.beta, 3), "retain_x": x_plan, "offloaded_layers": planned,
+                "retain_x_at_16k_tokens": lkv_b.plan_offload(cm, 16384)[0]}
+        if planned:
+            plan_bufs = {l: pinned[off_layers[i % len(off_layers)]] for i, l in enumerate(planned)}
+            eng.reset()
+            eng.begin_prompts(w.prompt_lens)
+            eng.prefill_all_layers(Qs, Ks, Vs, O, {})
+            torch.cuda.synchronize()
+            a, b = ev(), ev()
+            a.record(eng.d2h)
+            for l in planned:
+                eng.offload_layer(l, plan_bufs[l])
+            b.record(eng.d2h)
+            torch.cuda.synchronize()
+            t_link_plan = a.elapsed_time(b)          # the planned layers' pack + copy with nothing else running
+            prefill_phase(plan_bufs)                 # first run of a new pattern: not timed
+            _, t_both_plan = prefill_phase(plan_bufs)
+            plan.update({"offload_link_ms": round(t_link_plan, 3), "both_ms": round(t_both_plan, 3),
+                         "hidden_frac": round(max(0.0, min(1.0, 1 - (t_both_plan - t_compute) / t_link_plan)), 4)})
+        overlap["planned_by_lkv_plan_offload"] = plan
 
     # kernels alone, launched back to back (no other stream active, no events between launches)
     def alone(fn, launches, reps=3):

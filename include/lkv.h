@@ -154,6 +154,62 @@ int64_t lkv_num_free_blocks(const lkv_ctx *ctx);
  * the retained layers are 1,3,5,7 (the example of Section 3.2.2). */
 lkv_status lkv_plan_retained_layers(int32_t num_layers, int32_t x, int32_t *mask);
 
+/* ------------------------------------------------------------------ host-side policy (no context, no device)
+ * Pure functions of their arguments; times in seconds.  A time function returns NaN for invalid arguments. */
+
+/* Cost models of Section 3.1 (prefill time, the first equation labelled "prefill") and Section 3.2.1 (offload
+ * time, the second equation with that label). */
+typedef struct {
+  double alpha;             /* empirical correction of the prefill model                              */
+  double n_param;           /* model parameters                                                      */
+  double n_hidden;          /* hidden size                                                           */
+  double device_flops;      /* FLOP per second of the device                                         */
+  double beta;              /* empirical correction of the offload model                             */
+  int32_t num_layers;       /* L                                                                     */
+  int32_t head_dim;         /* d_heads                                                               */
+  int32_t num_heads;        /* n_heads: the heads whose K and V are stored (KV heads)                */
+  double bytes_per_elem;    /* f_precision in bytes                                                  */
+  double link_bytes_per_s;  /* PCIe bandwidth                                                        */
+} lkv_cost_model;
+/* alpha * seqlen * (2 n_param + 2 seqlen n_hidden) / device_flops */
+double lkv_prefill_time(const lkv_cost_model *m, int64_t seqlen);
+/* beta * seqlen * 2 (L - x) d_heads n_heads f_precision / link bandwidth: x layers stay on the GPU */
+double lkv_offload_time(const lkv_cost_model *m, int64_t seqlen, int32_t x);
+/* The smallest x in 0..L whose offload time does not exceed the prefill time of the same prompt (Section 3.2.1:
+ * the offload then hides behind the computation), and which layers stay: *x_out = x; retained_mask (host,
+ * num_layers entries, may be NULL) as lkv_plan_retained_layers gives it for that x. */
+lkv_status lkv_plan_offload(const lkv_cost_model *m, int64_t seqlen, int32_t *x_out, int32_t *retained_mask);
+
+/* One request in the decoding phase as the SLO-aware scheduler sees it (Section 3.1). */
+typedef struct {
+  double t_tpot;                  /* its TPOT target, seconds per token                               */
+  int64_t n_past;                 /* tokens generated so far                                          */
+  double t_past;                  /* decoding time spent so far, waiting included                     */
+  int64_t predicted_lower_bound;  /* lower bound of the predicted range of its complete output length */
+} lkv_decode_request;
+/* Eq. 1: T_tpot (N_past + N_future) - (T_past + T_future), with N_future = max(1, predicted_lower_bound -
+ * N_past) and T_future = current TPOT * N_future; the current TPOT is T_past / N_past, or the target for a
+ * request that has produced nothing yet. */
+double lkv_allow_prefill_time(const lkv_decode_request *r);
+/* Algorithm 1: *n_out = the largest n such that the prefill times of the first n queued requests (host array,
+ * queue order) add up to LESS than the smallest allowance of the decoding requests (host array); with nothing
+ * decoding the whole queue is admitted. */
+lkv_status lkv_max_prefills(const lkv_decode_request *decoding, int32_t num_decoding, const double *prefill_times,
+                            int32_t num_queued, int32_t *n_out);
+
+/* Free-block forecast (Section 3.2.1): Avail(t+1) = Avail(t) + Released(t) - Allocated(t) for `stages` stages
+ * from Avail(0) = avail0.  avail_out (host, `stages` entries, may be NULL) receives Avail(1..stages);
+ * *first_below (may be NULL) the first stage t >= 1 whose forecast is below `threshold`, or -1. */
+lkv_status lkv_forecast_avail(int64_t avail0, const int64_t *released, const int64_t *allocated, int32_t stages,
+                              int64_t threshold, int64_t *avail_out, int32_t *first_below);
+/* Pressure rule (Section 3.2.1): which retained layers to give up when `deficit_blocks` more free blocks are
+ * needed.  Requests are listed most recent first; retained[r] layers of request r are on the GPU, each holding
+ * blocks_per_layer[r] blocks.  First every request in turn gives half of its retained layers (rounded up)
+ * until the deficit is covered; only if all halves together are not enough do the requests, in the same order,
+ * give the rest.  give[r] (host) = layers request r gives up. */
+lkv_status lkv_pressure_offload(int64_t deficit_blocks, const int32_t *retained, const int64_t *blocks_per_layer,
+                                int32_t num_requests, int32_t *give);
+
 /* ------------------------------------------------------------------ device hot path */
 /* K, V: device, [num_tokens][num_kv_heads][head_dim], contiguous.  slot_mapping: device,
  * int64[num_tokens]; token t goes to slot slot_mapping[t]; a negative slot skips the token.

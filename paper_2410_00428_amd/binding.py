@@ -34,6 +34,8 @@ EXPORTS = (
     "lkv_paged_decode_attention",
     "lkv_stream_wait_event", "lkv_event_synchronize", "lkv_set_profiling", "lkv_get_stats",
     "lkv_probe_mfma_rate",
+    "lkv_prefill_time", "lkv_offload_time", "lkv_plan_offload", "lkv_allow_prefill_time", "lkv_max_prefills",
+    "lkv_forecast_avail", "lkv_pressure_offload",
 )
 
 
@@ -50,6 +52,20 @@ class LkvStats(ctypes.Structure):
                  "unpack_calls", "unpack_bytes", "pack_kernel_ns", "pack_kernel_bytes", "unpack_kernel_ns",
                  "unpack_kernel_bytes", "write_kernel_ns", "write_kernel_launches", "prefill_kernel_ns",
                  "prefill_kernel_launches", "decode_kernel_ns", "decode_kernel_launches")]
+
+
+class CostModel(ctypes.Structure):
+    """lkv_cost_model: the prefill-time and offload-time models of the paper (Sections 3.1, 3.2.1)."""
+    _fields_ = [("alpha", ctypes.c_double), ("n_param", ctypes.c_double), ("n_hidden", ctypes.c_double),
+                ("device_flops", ctypes.c_double), ("beta", ctypes.c_double), ("num_layers", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("num_heads", ctypes.c_int32), ("bytes_per_elem", ctypes.c_double),
+                ("link_bytes_per_s", ctypes.c_double)]
+
+
+class DecodeRequest(ctypes.Structure):
+    """lkv_decode_request: a decoding request as the SLO-aware scheduler sees it (Section 3.1)."""
+    _fields_ = [("t_tpot", ctypes.c_double), ("n_past", ctypes.c_int64), ("t_past", ctypes.c_double),
+                ("predicted_lower_bound", ctypes.c_int64)]
 
 
 class LkvError(RuntimeError):
@@ -104,6 +120,13 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "lkv_set_profiling": (i32, [vp, i32]),
         "lkv_get_stats": (i32, [vp, P(LkvStats), i64]),
         "lkv_probe_mfma_rate": (i32, [vp, ctypes.c_double, i32, P(ctypes.c_double), P(ctypes.c_double), vp]),
+        "lkv_prefill_time": (ctypes.c_double, [P(CostModel), i64]),
+        "lkv_offload_time": (ctypes.c_double, [P(CostModel), i64, i32]),
+        "lkv_plan_offload": (i32, [P(CostModel), i64, P(i32), vp]),
+        "lkv_allow_prefill_time": (ctypes.c_double, [P(DecodeRequest)]),
+        "lkv_max_prefills": (i32, [P(DecodeRequest), i32, P(ctypes.c_double), i32, P(i32)]),
+        "lkv_forecast_avail": (i32, [i64, vp, vp, i32, i64, vp, P(i32)]),
+        "lkv_pressure_offload": (i32, [i64, vp, vp, i32, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -138,6 +161,63 @@ def plan_retained_layers(num_layers: int, x: int) -> list:
     if st:
         raise LkvError(st, "lkv_plan_retained_layers: bad arguments")
     return [l for l in range(num_layers) if mask[l]]
+
+
+# ---------------------------------------------------------------------- host-side policy (no context)
+def prefill_time(model: CostModel, seqlen: int) -> float:
+    return load_library().lkv_prefill_time(ctypes.byref(model), seqlen)
+
+
+def offload_time(model: CostModel, seqlen: int, x: int) -> float:
+    return load_library().lkv_offload_time(ctypes.byref(model), seqlen, x)
+
+
+def plan_offload(model: CostModel, seqlen: int):
+    """(x, mask): the fewest layers to retain so that the offload hides behind the prefill, and which ones."""
+    x = ctypes.c_int32(0)
+    mask = np.zeros(max(model.num_layers, 1), dtype=np.int32)
+    st = load_library().lkv_plan_offload(ctypes.byref(model), seqlen, ctypes.byref(x), mask.ctypes.data)
+    if st:
+        raise LkvError(st, "lkv_plan_offload: bad arguments")
+    return x.value, mask[:model.num_layers]
+
+
+def allow_prefill_time(t_tpot: float, n_past: int, t_past: float, predicted_lower_bound: int) -> float:
+    r = DecodeRequest(t_tpot, n_past, t_past, predicted_lower_bound)
+    return load_library().lkv_allow_prefill_time(ctypes.byref(r))
+
+
+def max_prefills(decoding: Sequence[dict], prefill_times: Sequence[float]) -> int:
+    reqs = (DecodeRequest * max(len(decoding), 1))(*[DecodeRequest(**d) for d in decoding])
+    times = (ctypes.c_double * max(len(prefill_times), 1))(*prefill_times)
+    n = ctypes.c_int32(0)
+    st = load_library().lkv_max_prefills(reqs, len(decoding), times, len(prefill_times), ctypes.byref(n))
+    if st:
+        raise LkvError(st, "lkv_max_prefills: bad arguments")
+    return n.value
+
+
+def forecast_avail(avail0: int, released: Sequence[int], allocated: Sequence[int], threshold: int):
+    """(Avail(1..T), first stage below the threshold or -1)."""
+    rel = np.ascontiguousarray(released, dtype=np.int64)
+    alc = np.ascontiguousarray(allocated, dtype=np.int64)
+    out = np.zeros(max(len(rel), 1), dtype=np.int64)
+    first = ctypes.c_int32(0)
+    st = load_library().lkv_forecast_avail(avail0, rel.ctypes.data, alc.ctypes.data, len(rel), threshold, out.ctypes.data,
+                                           ctypes.byref(first))
+    if st:
+        raise LkvError(st, "lkv_forecast_avail: bad arguments")
+    return [int(v) for v in out[:len(rel)]], first.value
+
+
+def pressure_offload(deficit_blocks: int, retained: Sequence[int], blocks_per_layer: Sequence[int]) -> list:
+    x = np.ascontiguousarray(retained, dtype=np.int32)
+    b = np.ascontiguousarray(blocks_per_layer, dtype=np.int64)
+    give = np.zeros(max(len(x), 1), dtype=np.int32)
+    st = load_library().lkv_pressure_offload(deficit_blocks, x.ctypes.data, b.ctypes.data, len(x), give.ctypes.data)
+    if st:
+        raise LkvError(st, "lkv_pressure_offload: bad arguments")
+    return [int(v) for v in give[:len(x)]]
 
 
 class LKV:

@@ -204,7 +204,8 @@ def test_library_scheduler_matches_oracle():
             assert a == pytest.approx(float(b), rel=1e-12, abs=1e-12)
         assert lkv.max_prefills(reqs, queue) == po.max_prefills(allow_o, [F(q) for q in queue])
     assert lkv.max_prefills([], [1.0, 2.0]) == 2
-    assert lkv.max_prefills([dict(t_tpot=0.125, n_past=40, t_past=4.0, predicted_lower_bound=80)], [0.5, 0.25, 0.25]) == 2  # slack 1.0: 0.5+0.25 < 1
+    # pace 3/32 s per token against a target of 1/8: slack (1/8 - 3/32) * 64 = 2.0; 1 + 0.5 < 2, 1 + 0.5 + 0.5 is not
+    assert lkv.max_prefills([dict(t_tpot=0.125, n_past=32, t_past=3.0, predicted_lower_bound=64)], [1.0, 0.5, 0.5]) == 2
 
 
 def test_library_forecast_and_pressure_match_oracle():
