@@ -261,6 +261,42 @@ def main():
             s2["unpack_kernel_ns"] - s1["unpack_kernel_ns"], 1)
         iso["offload_GBps"] = layer_bytes * len(off_layers) / (t_link * 1e-3) / 1e9
         iso["reload_GBps"] = layer_bytes * len(off_layers) / (t_reload * 1e-3) / 1e9
+        # the same layers through the pageable tier: ordinary host memory behind the library's small pinned ring
+        import numpy as np
+        pageable = np.ones(layer_bytes * len(off_layers), dtype=np.uint8)   # touched before timing
+        views = {l: pageable[i * layer_bytes:(i + 1) * layer_bytes] for i, l in enumerate(off_layers)}
+        t_page = {}
+        for rep in range(2):                                                # first pass builds the ring
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for l in off_layers:
+                eng.offload_layer_pageable(l, views[l])
+            eng.ctx.host_tier_synchronize()
+            t_page["offload"] = time.perf_counter() - t0
+            same = all(bytes(views[l][:4096]) == bytes(pinned[l][:4096].numpy()) and
+                       bytes(views[l][-4096:]) == bytes(pinned[l][layer_bytes - 4096:layer_bytes].numpy())
+                       for l in off_layers)
+            for l in off_layers:
+                eng.release_offloaded(l)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for l in off_layers:
+                eng.reload_layer(l)
+            torch.cuda.synchronize()
+            t_page["reload"] = time.perf_counter() - t0
+        s3 = eng.ctx.get_stats()
+        for l in off_layers:
+            eng.host_images[l] = pinned[l]
+        iso["pageable_tier"] = {
+            "offload_GBps": round(layer_bytes * len(off_layers) / t_page["offload"] / 1e9, 2),
+            "reload_GBps": round(layer_bytes * len(off_layers) / t_page["reload"] / 1e9, 2),
+            "pinned_ring_MiB": 128, "host_image_MiB": pageable.nbytes >> 20,
+            "memcpy_GBps_per_thread": round(s3["tier_copy_bytes"] / max(s3["tier_copy_ns"], 1), 1),
+            "image_ends_equal_pinned_path": bool(same),
+            "note": "lkv_offload_layer_pageable / lkv_reload_layer_pageable: wall time until the image is complete "
+                    "in ordinary host memory (4 CPU threads drain 4 pinned units of 32 MiB), resp. until the blocks "
+                    "are back in the pool"}
+        del pageable, views
         _, t_both = prefill_phase(True)
         # only the compute issued after the first offload can hide anything
         t_hideable = t_compute * (L - 1 - first_off) / L
@@ -332,7 +368,7 @@ def main():
     iso["write_kv_GBps"] = 2 * T * sh.token_bytes / (t_write * 1e-3) / 1e9
     iso["prefill_attn_TFLOPs"] = pf_flops / (t_prefill * 1e-3) / 1e12
     iso["decode_paged_attn_GBps"] = decode_bytes_per_launch[0] / (t_decode * 1e-3) / 1e9
-    iso = {k: round(v, 2) for k, v in iso.items()}
+    iso = {k: (round(v, 2) if isinstance(v, float) else v) for k, v in iso.items()}
     traffic = TRAFFIC_BYTES.get(args.workload)
     # what a pure bf16 MFMA stream sustains on this machine right now (random operand bits, as in real data; then
     # constant operands): the published peak assumes the boost clock, which a matrix load does not hold

@@ -111,6 +111,15 @@ typedef struct {
   int64_t write_kernel_ns, write_kernel_launches;
   int64_t prefill_kernel_ns, prefill_kernel_launches;
   int64_t decode_kernel_ns, decode_kernel_launches;
+  /* pageable host tier: calls and bytes of lkv_offload_layer_pageable / lkv_reload_layer_pageable; bytes the
+   * CPU threads have copied between the pinned ring and pageable memory and the time they spent in memcpy
+   * (summed over threads); time the calling thread waited for a free ring unit; how often the link gate
+   * answered "busy" (lkv_set_link_gate) */
+  int64_t pageable_offload_calls, pageable_offload_bytes;
+  int64_t pageable_reload_calls, pageable_reload_bytes;
+  int64_t tier_copy_bytes, tier_copy_ns;
+  int64_t ring_wait_ns;
+  int64_t gate_busy_answers;
 } lkv_stats;
 
 /* ------------------------------------------------------------------ life cycle */
@@ -241,6 +250,45 @@ lkv_status lkv_pack_layer_blocks(lkv_ctx *ctx, int32_t layer, const int32_t *blo
 lkv_status lkv_unpack_layer_blocks(lkv_ctx *ctx, int32_t layer, const int32_t *block_ids, int64_t n,
                                    const void *pinned_src, void *stream);
 
+/* ---- pageable host tier (Section 4: a CPU thread moves offloaded KV from pinned to pageable memory;
+ * Section 3.2.3: a transfer is cut into smaller units).  The two calls below move the same image as
+ * lkv_pack_layer_blocks / lkv_unpack_layer_blocks, but to and from ORDINARY host memory: the data crosses the
+ * link through a small ring of pinned units owned by the library, and CPU threads of the library copy between
+ * the ring and the caller's buffer, so pinned memory stays at num_units*unit_bytes however much KV is
+ * offloaded.  The calling thread blocks while all ring units are in use (that is the back-pressure of a
+ * bounded ring), never for the link or the memcpy of a unit it has already handed over. */
+
+/* Sets the ring's shape: unit_bytes per unit (rounded down to whole blocks, at least one block, at most the
+ * device staging), num_units >= 1 units of pinned memory, threads >= 1 CPU threads.  Zero keeps the default
+ * (32 MiB, 4 units, 4 threads).  Allowed any time: waits for the tier's outstanding work, then rebuilds the
+ * ring.  Without this call the ring is built with the defaults on first use. */
+lkv_status lkv_host_tier_config(lkv_ctx *ctx, int64_t unit_bytes, int32_t num_units, int32_t threads);
+/* Offload to pageable memory: as lkv_pack_layer_blocks (same waits, same events on `stream`), with host_dst
+ * (n*beta bytes) ordinary host memory.  LKV_EV_OFFLOADED here means "the last unit has reached the pinned
+ * ring"; the image is complete in host_dst once lkv_host_tier_synchronize(layer) or
+ * lkv_event_synchronize(layer, LKV_EV_OFFLOADED) has returned.  host_dst must stay valid until then.  A
+ * second offload of the same layer first waits for the first one's CPU copies. */
+lkv_status lkv_offload_layer_pageable(lkv_ctx *ctx, int32_t layer, const int32_t *block_ids, int64_t n,
+                                      void *host_dst, void *stream);
+/* Reload from pageable memory: as lkv_unpack_layer_blocks, with host_src ordinary host memory.  Waits (host)
+ * for outstanding CPU copies of an offload of the same layer, then per unit: CPU copy into a ring unit (split
+ * over the library's threads and the caller), host-to-device copy, scatter.  host_src may be reused when the
+ * call returns.  Records LKV_EV_RELOADED on `stream`. */
+lkv_status lkv_reload_layer_pageable(lkv_ctx *ctx, int32_t layer, const int32_t *block_ids, int64_t n,
+                                     const void *host_src, void *stream);
+/* Blocks until the CPU copies of every pageable offload of `layer` issued so far are done (layer -1: of all
+ * layers).  LKV_ERR_DEVICE if waiting for one of their device copies failed. */
+lkv_status lkv_host_tier_synchronize(lkv_ctx *ctx, int32_t layer);
+
+/* Link gate (Section 3.2.3: before a swap, check whether the host link is in use by traffic on the critical
+ * path; if so wait a while and check again, unit by unit).  busy(user) is called on the calling thread before
+ * every unit of all four transfer calls (a unit is a staging chunk for pack/unpack, a ring unit for the
+ * pageable calls); while it returns non-zero the library sleeps delay_us microseconds and asks again, at most
+ * max_checks times per unit (then the unit goes anyway, so a gate that never opens cannot stop the transfer).
+ * busy == NULL removes the gate.  delay_us >= 0, max_checks >= 0. */
+typedef int32_t (*lkv_link_busy_fn)(void *user);
+lkv_status lkv_set_link_gate(lkv_ctx *ctx, lkv_link_busy_fn busy, void *user, int64_t delay_us, int32_t max_checks);
+
 /* Decode attention through this layer's block table (Sections 2.1.2, 2.2, 3.2.2).  Q, O:
  * device, [num_seqs][num_q_heads][head_dim]; block_table: device, int32[num_seqs][max_blocks_per_seq]
  * (entries past ceil(context_len/bs) are ignored; every entry before that must be a block id of the pool: the
@@ -257,7 +305,8 @@ lkv_status lkv_paged_decode_attention(lkv_ctx *ctx, int32_t layer, const void *Q
 /* ------------------------------------------------------------------ ordering and statistics */
 /* Makes `stream` wait for the last recorded event `ev` of `layer` (no-op if never recorded). */
 lkv_status lkv_stream_wait_event(lkv_ctx *ctx, int32_t layer, int32_t ev, void *stream);
-/* Blocks the host until that event has happened. */
+/* Blocks the host until that event has happened (for LKV_EV_OFFLOADED of a pageable offload: until the image
+ * is complete in the caller's buffer). */
 lkv_status lkv_event_synchronize(lkv_ctx *ctx, int32_t layer, int32_t ev);
 /* Turns per-launch HIP-event timing of the library's kernels on or off (off by default; each timed launch
  * costs two extra event records).  Results accumulate in lkv_stats. */

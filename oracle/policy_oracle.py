@@ -122,3 +122,19 @@ def pressure_offload(deficit_blocks: int, retained: Sequence[int], blocks_per_la
         freed += (x - give[r]) * b
         give[r] = x
     return give
+
+
+# ----------------------------------------------------------------------------- Section 3.2.3, link check per sub-unit
+def gated_units(answers: Sequence[bool], units: int, max_checks: int) -> Tuple[int, int]:
+    """Before each of `units` sub-units the link is asked whether it is busy; a busy answer delays and asks again,
+    at most max_checks questions per unit, after which the unit goes anyway.  `answers` is the sequence of replies
+    in the order asked (True = busy; exhausted = free).  Returns (questions asked, busy answers = delays)."""
+    it = iter(answers)
+    asked = busy = 0
+    for _ in range(units):
+        for _ in range(max_checks):
+            asked += 1
+            if not next(it, False):
+                break
+            busy += 1
+    return asked, busy

@@ -32,6 +32,8 @@ EXPORTS = (
     "lkv_plan_retained_layers",
     "lkv_write_kv", "lkv_prefill_attention", "lkv_pack_layer_blocks", "lkv_unpack_layer_blocks",
     "lkv_paged_decode_attention",
+    "lkv_host_tier_config", "lkv_offload_layer_pageable", "lkv_reload_layer_pageable", "lkv_host_tier_synchronize",
+    "lkv_set_link_gate",
     "lkv_stream_wait_event", "lkv_event_synchronize", "lkv_set_profiling", "lkv_get_stats",
     "lkv_probe_mfma_rate",
     "lkv_prefill_time", "lkv_offload_time", "lkv_plan_offload", "lkv_allow_prefill_time", "lkv_max_prefills",
@@ -51,7 +53,12 @@ class LkvStats(ctypes.Structure):
                 ("write_kv_calls", "write_kv_bytes", "prefill_calls", "decode_calls", "pack_calls", "pack_bytes",
                  "unpack_calls", "unpack_bytes", "pack_kernel_ns", "pack_kernel_bytes", "unpack_kernel_ns",
                  "unpack_kernel_bytes", "write_kernel_ns", "write_kernel_launches", "prefill_kernel_ns",
-                 "prefill_kernel_launches", "decode_kernel_ns", "decode_kernel_launches")]
+                 "prefill_kernel_launches", "decode_kernel_ns", "decode_kernel_launches",
+                 "pageable_offload_calls", "pageable_offload_bytes", "pageable_reload_calls", "pageable_reload_bytes",
+                 "tier_copy_bytes", "tier_copy_ns", "ring_wait_ns", "gate_busy_answers")]
+
+
+LINK_BUSY_FN = ctypes.CFUNCTYPE(ctypes.c_int32, ctypes.c_void_p)
 
 
 class CostModel(ctypes.Structure):
@@ -115,6 +122,11 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "lkv_pack_layer_blocks": (i32, [vp, i32, vp, i64, vp, vp]),
         "lkv_unpack_layer_blocks": (i32, [vp, i32, vp, i64, vp, vp]),
         "lkv_paged_decode_attention": (i32, [vp, i32, vp, vp, vp, i32, vp, i32, vp]),
+        "lkv_host_tier_config": (i32, [vp, i64, i32, i32]),
+        "lkv_offload_layer_pageable": (i32, [vp, i32, vp, i64, vp, vp]),
+        "lkv_reload_layer_pageable": (i32, [vp, i32, vp, i64, vp, vp]),
+        "lkv_host_tier_synchronize": (i32, [vp, i32]),
+        "lkv_set_link_gate": (i32, [vp, LINK_BUSY_FN, vp, i64, i32]),
         "lkv_stream_wait_event": (i32, [vp, i32, i32, vp]),
         "lkv_event_synchronize": (i32, [vp, i32, i32]),
         "lkv_set_profiling": (i32, [vp, i32]),
@@ -144,6 +156,8 @@ def _ptr(x) -> int:
         return x
     if hasattr(x, "data_ptr"):
         return x.data_ptr()
+    if isinstance(x, np.ndarray):
+        return x.ctypes.data
     raise TypeError(f"cannot take the address of {type(x)}")
 
 
@@ -334,6 +348,35 @@ class LKV:
         ids = np.ascontiguousarray(block_ids, dtype=np.int32)
         self._check(self.lib.lkv_unpack_layer_blocks(self.h, layer, ids.ctypes.data, ids.size, _ptr(pinned_src),
                                                      _stream(stream)))
+
+    # ------------------------------------------------------------------ pageable host tier
+    def host_tier_config(self, unit_bytes: int = 0, num_units: int = 0, threads: int = 0) -> None:
+        self._check(self.lib.lkv_host_tier_config(self.h, unit_bytes, num_units, threads))
+
+    def offload_layer_pageable(self, layer: int, block_ids, host_dst, stream=None) -> None:
+        """host_dst: ordinary host memory (numpy array, CPU tensor or address) that stays alive until
+        ``host_tier_synchronize(layer)`` has returned."""
+        ids = np.ascontiguousarray(block_ids, dtype=np.int32)
+        self._check(self.lib.lkv_offload_layer_pageable(self.h, layer, ids.ctypes.data, ids.size, _ptr(host_dst),
+                                                        _stream(stream)))
+
+    def reload_layer_pageable(self, layer: int, block_ids, host_src, stream=None) -> None:
+        ids = np.ascontiguousarray(block_ids, dtype=np.int32)
+        self._check(self.lib.lkv_reload_layer_pageable(self.h, layer, ids.ctypes.data, ids.size, _ptr(host_src),
+                                                       _stream(stream)))
+
+    def host_tier_synchronize(self, layer: int = -1) -> None:
+        self._check(self.lib.lkv_host_tier_synchronize(self.h, layer))
+
+    def set_link_gate(self, busy=None, delay_us: int = 0, max_checks: int = 0) -> None:
+        """busy: a callable without arguments returning True while the host link is taken, or None."""
+        if busy is None:
+            self._gate = None
+            self._check(self.lib.lkv_set_link_gate(self.h, LINK_BUSY_FN(), None, 0, 0))
+            return
+        cb = LINK_BUSY_FN(lambda _user: 1 if busy() else 0)
+        self._check(self.lib.lkv_set_link_gate(self.h, cb, None, delay_us, max_checks))
+        self._gate = cb  # the library keeps the pointer: keep the thunk alive
 
     def paged_decode_attention(self, layer: int, Q, O, block_table, max_blocks_per_seq: int, context_lens,
                                num_seqs: int, stream=None) -> None:

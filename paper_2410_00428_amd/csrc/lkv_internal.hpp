@@ -8,6 +8,7 @@
 #include <unordered_map>
 #include <vector>
 
+#include "host_tier.hpp"
 #include "lkv.h"
 
 namespace lkv {
@@ -75,6 +76,16 @@ struct lkv_ctx {
     int64_t bytes;
     int kind;
   };
+  // pageable host tier: pinned ring, one event per ring unit, the CPU threads
+  lkv::HostTier tier;
+  char *ring = nullptr;
+  std::vector<hipEvent_t> unit_ev;
+  int64_t unit_blocks = 0;
+  // link gate
+  lkv_link_busy_fn gate_busy = nullptr;
+  void *gate_user = nullptr;
+  int64_t gate_delay_us = 0;
+  int32_t gate_max_checks = 0;
   bool profiling = false;
   std::vector<Timed> timed;
   std::vector<hipEvent_t> spare_events;

@@ -116,6 +116,13 @@ class LayerKVEngine:
         self._timed("offload", self.d2h, lambda: self.ctx.pack_layer_blocks(layer, ids, buf, self.d2h))
         self.host_images[layer] = buf
 
+    def offload_layer_pageable(self, layer: int, buf: np.ndarray) -> None:
+        """The same image into ordinary host memory (Section 4: pinned memory is only a small ring that CPU
+        threads of the library drain); complete once ``ctx.host_tier_synchronize(layer)`` has returned."""
+        ids = self.layer_block_ids(layer)
+        self._timed("offload", self.d2h, lambda: self.ctx.offload_layer_pageable(layer, ids, buf, self.d2h))
+        self.host_images[layer] = buf
+
     def release_offloaded(self, layer: int) -> None:
         """The layer's blocks go back to the free list (host logic); the data lives on the host now.
         The main stream is ordered behind the gather so that whoever reuses the blocks writes later."""
@@ -131,10 +138,13 @@ class LayerKVEngine:
         c = self.ctx
         lens = lens or self.lens
         buf = self.host_images[layer]
-        c.stream_wait_event(layer, lkv.LKV_EV_OFFLOADED, self.h2d)   # the image must be complete on the host
         for s, n in enumerate(lens):
             c.alloc_layer_blocks(s, layer, n)
         ids = self.layer_block_ids(layer)
+        if isinstance(buf, np.ndarray):   # pageable image: the library waits for its own CPU copies
+            self._timed("reload", self.h2d, lambda: c.reload_layer_pageable(layer, ids, buf, self.h2d))
+            return
+        c.stream_wait_event(layer, lkv.LKV_EV_OFFLOADED, self.h2d)   # the image must be complete on the host
         self._timed("reload", self.h2d, lambda: c.unpack_layer_blocks(layer, ids, buf, self.h2d))
 
     def map_decode_layer(self, layer: int, step: int):

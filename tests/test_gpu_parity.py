@@ -368,3 +368,114 @@ def test_mfma_probe_reports_a_plausible_rate_and_clock():
         assert 0.85 * pipe_rate < tf < 1.02 * pipe_rate, (tf, mhz, pipe_rate)
     assert tf_c > 0.9 * tf_r
     c.destroy()
+
+
+# ----------------------------------------------------------------------------- pageable host tier
+def _random_pool(shape, nblk, seed, **kw):
+    c, o, pool = H.make_pair(shape, nblk, wl.free_list_order(seed, nblk), **kw)
+    rng = np.random.default_rng(seed)
+    o.pool[:] = rng.integers(0, 2 ** 16, size=o.pool.shape, dtype=np.uint16)
+    pool.copy_(torch.from_numpy(o.pool.view(np.uint8).reshape(-1)).to(H.DEV))
+    torch.cuda.synchronize()
+    return c, o, pool, rng
+
+
+@pytest.mark.parametrize("unit_blocks,units,threads", [(3, 2, 2), (1, 1, 1), (64, 8, 4)])
+def test_pageable_offload_and_reload_through_a_small_pinned_ring(unit_blocks, units, threads):
+    """Section 4: offload image lands in ordinary host memory through a bounded pinned ring drained by CPU
+    threads; bytes equal the oracle's pack image, and reloading it into other blocks equals the oracle's unpack."""
+    shape = wl.KVShape(2, 4, 4, 64, 16, "bf16")   # block = 16 KiB
+    nblk = 128
+    c, o, pool, rng = _random_pool(shape, nblk, 31, staging_bytes=5 * shape.block_bytes)
+    c.host_tier_config(unit_blocks * shape.block_bytes, units, threads)
+    side = torch.cuda.Stream()
+    ids = rng.permutation(nblk)[:50].astype(np.int32)
+    image = np.full(50 * shape.block_bytes + 64, 0xA5, dtype=np.uint8)   # ordinary memory, with a guard tail
+    c.offload_layer_pageable(1, ids, image, side)
+    c.host_tier_synchronize(1)
+    ref = o.pack_layer_blocks(ids)
+    assert image[:-64].tobytes() == ref.tobytes()
+    assert (image[-64:] == 0xA5).all()
+    st = c.get_stats()
+    assert st["pageable_offload_calls"] == 1 and st["pageable_offload_bytes"] == 50 * shape.block_bytes
+    assert st["tier_copy_bytes"] >= 50 * shape.block_bytes
+    new_ids = rng.permutation(nblk)[:50].astype(np.int32)
+    c.reload_layer_pageable(1, new_ids, image, side)
+    image[:] = 0   # the source may be reused as soon as the call has returned
+    o.unpack_layer_blocks(new_ids, ref.copy())
+    c.event_synchronize(1, lkv.LKV_EV_RELOADED)
+    assert H.pool_as_oracle_view(pool, o).tobytes() == o.pool.tobytes()
+    # empty transfers are legal and leave nothing pending
+    c.offload_layer_pageable(0, np.zeros(0, np.int32), None, side)
+    c.reload_layer_pageable(0, np.zeros(0, np.int32), None, side)
+    c.event_synchronize(0, lkv.LKV_EV_OFFLOADED)
+    c.destroy()
+
+
+def test_pageable_offload_of_many_layers_back_to_back_and_repeated_layer():
+    """Several layers queued behind each other on the transfer stream with fewer ring units than units in
+    flight; waiting for one layer's event completes that layer's image; a second offload of a layer into the
+    same buffer after its blocks changed gives the new bytes (the library orders the two)."""
+    shape = wl.KVShape(6, 2, 2, 64, 16, "bf16")   # block = 8 KiB
+    nblk = 96
+    c, o, pool, rng = _random_pool(shape, nblk, 32)
+    c.host_tier_config(4 * shape.block_bytes, 3, 3)
+    side = torch.cuda.Stream()
+    per_layer = {l: rng.permutation(nblk)[:5 + 7 * l].astype(np.int32) for l in range(6)}
+    images = {l: np.zeros(len(ids) * shape.block_bytes, np.uint8) for l, ids in per_layer.items()}
+    for l, ids in per_layer.items():
+        c.offload_layer_pageable(l, ids, images[l], side)
+    c.event_synchronize(2, lkv.LKV_EV_OFFLOADED)
+    assert images[2].tobytes() == o.pack_layer_blocks(per_layer[2]).tobytes()
+    c.host_tier_synchronize()
+    for l, ids in per_layer.items():
+        assert images[l].tobytes() == o.pack_layer_blocks(ids).tobytes(), f"layer {l}"
+    # change the blocks of layer 5 on both sides, offload it twice in a row into the same buffer
+    o.pool[:] = rng.integers(0, 2 ** 16, size=o.pool.shape, dtype=np.uint16)
+    c.offload_layer_pageable(5, per_layer[5], images[5], side)   # old bytes, still draining ...
+    side.synchronize()
+    pool.copy_(torch.from_numpy(o.pool.view(np.uint8).reshape(-1)).to(H.DEV))
+    torch.cuda.synchronize()
+    c.offload_layer_pageable(5, per_layer[5], images[5], side)   # ... when the new ones are requested
+    c.host_tier_synchronize(5)
+    assert images[5].tobytes() == o.pack_layer_blocks(per_layer[5]).tobytes()
+    c.destroy()
+
+
+def test_link_gate_is_asked_before_every_unit_and_cannot_stop_a_transfer():
+    """Section 3.2.3: the link is checked per sub-unit; a busy answer delays that unit only.  Question and
+    delay counts follow the oracle's closed form; the bytes moved are unaffected."""
+    from oracle import policy_oracle as po
+    shape = wl.KVShape(1, 2, 2, 64, 16, "bf16")
+    nblk = 64
+    c, o, pool, rng = _random_pool(shape, nblk, 33, staging_bytes=4 * shape.block_bytes)
+    c.host_tier_config(2 * shape.block_bytes, 2, 2)
+    ids = rng.permutation(nblk)[:9].astype(np.int32)   # pack: 3 staging chunks; pageable: 5 ring units
+    ref = o.pack_layer_blocks(ids)
+    for pageable, units in ((False, 3), (True, 5)):
+        for answers, max_checks in (([], 4), ([True, True, False, True], 4), ([True] * 100, 3)):
+            asked = []
+            seq = iter(answers)
+
+            def busy():
+                asked.append(1)
+                return next(seq, False)
+            before = c.get_stats()["gate_busy_answers"]
+            c.set_link_gate(busy, delay_us=50, max_checks=max_checks)
+            if pageable:
+                image = np.zeros(ref.nbytes, np.uint8)
+                c.offload_layer_pageable(0, ids, image)
+                c.host_tier_synchronize(0)
+                got = image.tobytes()
+            else:
+                buf = H.pinned_bytes(ref.nbytes)
+                c.pack_layer_blocks(0, ids, buf)
+                c.event_synchronize(0, lkv.LKV_EV_OFFLOADED)
+                got = buf.numpy()[:ref.nbytes].tobytes()
+            want_asked, want_busy = po.gated_units(answers, units, max_checks)
+            assert (len(asked), c.get_stats()["gate_busy_answers"] - before) == (want_asked, want_busy)
+            assert got == ref.tobytes()
+    c.set_link_gate(None)
+    c.pack_layer_blocks(0, ids, H.pinned_bytes(ref.nbytes))
+    torch.cuda.synchronize()
+    c.destroy()

@@ -176,3 +176,38 @@ def test_fragmenting_schedule_gives_fragmented_identical_tables():
     assert jumps / total >= 0.5
     assert c.get_block_table(0, 0).tolist() != c.get_block_table(0, 1).tolist()
     c.destroy()
+
+
+@pytest.mark.parametrize("threads,units", [(3, 3), (1, 1), (4, 2)])
+def test_pinned_ring_and_drain_threads_under_a_thread_sanitizer(tmp_path, threads, units):
+    """The bounded ring of transfer units and its CPU threads (Section 4), without a GPU: a stand-in copy engine
+    fills units, workers drain them into per-layer images; every image complete and exact, every unit handed back
+    once, split memcpy exact, a failed wait reported; the build's thread sanitizer must stay silent."""
+    import shutil
+    import subprocess
+    if shutil.which("g++") is None:
+        pytest.skip("no host compiler")
+    exe = str(tmp_path / "host_tier_test")
+    src = os.path.join(ROOT, "tests", "native", "host_tier_test.cpp")
+    inc = os.path.join(ROOT, "paper_2410_00428_amd", "csrc")
+    subprocess.run(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=thread", "-I", inc, src, "-o", exe, "-lpthread"],
+                   check=True)
+    r = subprocess.run([exe, str(threads), str(units)], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "ThreadSanitizer" not in r.stderr
+    assert "host_tier_test: ok" in r.stdout
+
+
+def test_tier_and_gate_calls_validate_arguments_without_a_device():
+    c = logical()
+    for call in (lambda: c.host_tier_config(0, 0, 0), lambda: c.host_tier_synchronize(0),
+                 lambda: c.offload_layer_pageable(0, [0], np.zeros(8, np.uint8)),
+                 lambda: c.reload_layer_pageable(0, [0], np.zeros(8, np.uint8))):
+        with pytest.raises(lkv.LkvError) as e:
+            call()
+        assert e.value.status == lkv.LKV_ERR_DEVICE
+    with pytest.raises(lkv.LkvError) as e:
+        c.set_link_gate(lambda: False, delay_us=-1)
+    assert e.value.status == lkv.LKV_ERR_INVALID_ARG
+    c.set_link_gate(lambda: False, delay_us=0, max_checks=3)   # host state only: allowed
+    c.set_link_gate(None)

@@ -222,3 +222,14 @@ def test_library_forecast_and_pressure_match_oracle():
         b = [rng.randint(1, 20) for _ in range(R)]
         d = rng.randint(-5, 300)
         assert lkv.pressure_offload(d, x, b) == po.pressure_offload(d, x, b)
+
+
+def test_gated_units_closed_forms():
+    """Section 3.2.3: a free link costs one question per unit and no delay; a link that never frees costs the
+    bound per unit; k busy answers before a free one delay exactly k times."""
+    assert po.gated_units([], 7, 5) == (7, 0)
+    assert po.gated_units([True] * 1000, 7, 5) == (35, 35)
+    assert po.gated_units([True, True, False], 1, 5) == (3, 2)
+    assert po.gated_units([True, True, False, True, False], 3, 5) == (6, 3)
+    assert po.gated_units([True] * 9, 4, 0) == (0, 0)   # no question allowed: ungated
+    assert po.gated_units([], 0, 5) == (0, 0)
