@@ -470,8 +470,9 @@ prefill_bf16_d128_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restr
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) ka[kk] = kread(TB, kk);
 
-    // softmax of one unit's scores: probabilities (bf16, B-operand layout of the second product), running
-    // max / sum; the output accumulators are rescaled only when some running maximum grew
+    // softmax of one unit's scores: probabilities (bf16, B-operand layout of the second product), reference
+    // maximum / sum
+    constexpr float kLazy = 8.f;
     auto softmax = [&](f32x16 &sc, bf16x8 (&pb)[2], bool need_mask, int k0) {
       if (need_mask) {
 #pragma unroll
@@ -484,11 +485,23 @@ prefill_bf16_d128_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restr
 #pragma unroll
       for (int v = 2; v < 16; ++v) mx = fmaxf(mx, sc[v]);
       mx = both_max(mx);
-      const float m_new = fmaxf(m, mx);
-      const float ms = (m_new == -INFINITY ? 0.f : m_new) * scale_log2e;
-      const float alpha = __builtin_amdgcn_exp2f(m * scale_log2e - ms);
-      const bool grew = m_new > m;
-      m = m_new;
+      // m is the REFERENCE of the exponentials, in scaled log2 units.  It follows the running maximum lazily: it
+      // only moves when a score exceeds it by more than kLazy, so probabilities stay below 2^kLazy (exact in
+      // fp32 sums and as bf16 operands: both keep their relative precision at that magnitude) and the 64 output
+      // accumulators are rescaled a few times per row instead of whenever any of a wavefront's 32 running maxima
+      // grows (three units out of four at 2048 keys).  The quotient O / l does not depend on the reference.
+      const float mxs = mx * scale_log2e;
+      const bool grew = mxs > m + kLazy;
+      if (__any(grew)) {
+        const float alpha = grew ? __builtin_amdgcn_exp2f(m - mxs) : 1.f;  // m = -inf on first use: 0
+        m = grew ? mxs : m;
+        lsum *= alpha;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
+      }
+      const float ms = m == -INFINITY ? 0.f : m;  // a row that has seen no key yet: exp2(-inf - 0) = 0
       float psum = 0.f;
       float p[16];
 #pragma unroll
@@ -496,19 +509,13 @@ prefill_bf16_d128_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restr
         p[v] = __builtin_amdgcn_exp2f(fmaf(sc[v], scale_log2e, -ms));
         psum += p[v];
       }
-      lsum = lsum * alpha + psum;
+      lsum += psum;
 #pragma unroll
       for (int sl = 0; sl < 2; ++sl) {
         u32x4 pw;
 #pragma unroll
         for (int e = 0; e < 4; ++e) pw[e] = pack_bf16(p[8 * sl + 2 * e], p[8 * sl + 2 * e + 1]);
         pb[sl] = __builtin_bit_cast(bf16x8, pw);
-      }
-      if (__any(grew)) {
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
       }
     };
 
