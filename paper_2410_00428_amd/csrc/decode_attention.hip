@@ -11,8 +11,6 @@
 // each group of lanes that shares a token sub-row keeps its own running (max, sum, output) and
 // the groups, then the wavefronts, then the partitions are merged with the usual
 // exp(m_i - m) weights.
-#include <cstdio>
-#include <cstdlib>
 
 #include "lkv_internal.hpp"
 
@@ -393,7 +391,7 @@ __device__ __forceinline__ void decode_work_item(const int32_t *__restrict__ con
   }
 }
 
-template <int G, int WAVES, bool PREFETCH>
+template <int G, int WAVES>
 __global__ void __launch_bounds__(WAVES * 64)
 paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, const char *__restrict__ pool,
                          const int32_t *__restrict__ block_table, int max_blocks,
@@ -513,22 +511,15 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
       }
     };
 
-    if (PREFETCH) {
-      u32x4 kxa[4], kya[4], va[8], kxb[4], kyb[4], vb[8];
-      load(0, kxa, kya, va);
-      for (int it = 0; it < cnt; it += 2) {
-        if (it + 1 < cnt) load(it + 1, kxb, kyb, vb);
-        compute(it, kxa, kya, va);
-        if (it + 1 < cnt) {
-          if (it + 2 < cnt) load(it + 2, kxa, kya, va);
-          compute(it + 1, kxb, kyb, vb);
-        }
-      }
-    } else {
-      u32x4 kxa[4], kya[4], va[8];
-      for (int it = 0; it < cnt; ++it) {
-        load(it, kxa, kya, va);
-        compute(it, kxa, kya, va);
+    // two block pairs in flight per wavefront: the next pair's loads are issued before the current pair's math
+    u32x4 kxa[4], kya[4], va[8], kxb[4], kyb[4], vb[8];
+    load(0, kxa, kya, va);
+    for (int it = 0; it < cnt; it += 2) {
+      if (it + 1 < cnt) load(it + 1, kxb, kyb, vb);
+      compute(it, kxa, kya, va);
+      if (it + 1 < cnt) {
+        if (it + 2 < cnt) load(it + 2, kxa, kya, va);
+        compute(it + 1, kxb, kyb, vb);
       }
     }
   }
@@ -604,38 +595,25 @@ decode_combine_kernel(T *__restrict__ O, const int32_t *__restrict__ context_len
 // and with the partition fastest a short last partition (e.g. 2049 = 2048 + 1 tokens) would put all
 // the heavy workgroups on half of the XCDs.
 struct Plan {
-  int partition, num_parts, waves;
-  bool mfma, prefetch;
+  int partition, num_parts;
+  bool mfma;
   bool lpt;  // workgroups take the launch's (sequence, partition) items longest first (see decode_work_item)
 };
 
 Plan make_plan(const lkv_ctx *c, int num_seqs, int max_blocks) {
   const int64_t tokens = (int64_t)max_blocks * kBlock;
   const int64_t units = (int64_t)num_seqs * c->cfg.num_kv_heads;
-  Plan p{0, 1, 4, false, true, false};
+  Plan p{0, 1, false, false};
   p.mfma = c->cfg.dtype == LKV_BF16 && c->cfg.head_dim == 128;
   if (p.mfma) {
     // measured on MI355X over the four decode workloads: 8 wavefronts per workgroup, two block pairs in
     // flight per wavefront, partitions of 4096 tokens (contexts up to 4096 are not split at all)
-    p.waves = 8;
     p.partition = 4096;
   } else {
     p.partition = 512;
     while (p.partition > 128 && units * ((tokens + p.partition - 1) / p.partition) < 2048) p.partition >>= 1;
   }
   if (c->cfg.decode_partition > 0) p.partition = c->cfg.decode_partition;
-  if (const char *t = getenv("LKV_DECODE_TUNE")) {  // development aid: "partition,waves,mfma,prefetch"
-    int a = 0, b = 0, m = 0, pf = 1;
-    if (sscanf(t, "%d,%d,%d,%d", &a, &b, &m, &pf) >= 2 && a > 0 && a % 64 == 0 &&
-        (b == 1 || b == 2 || b == 4 || b == 8 || b == 16)) {
-      p.partition = a;
-      p.waves = b;
-      p.mfma = m != 0 && p.mfma;
-      p.prefetch = pf != 0;
-    }
-  }
-  if (p.mfma && p.waves > 8) p.waves = 8;
-  if (!p.mfma && p.waves < 4) p.waves = 4;
   p.num_parts = (int)((tokens + p.partition - 1) / p.partition);
   if (p.num_parts < 1) p.num_parts = 1;
   // Longest-first order pays when the launch is only a few rounds of workgroups deep: measured on a ragged
@@ -663,14 +641,9 @@ hipError_t launch_mfma(const lkv_ctx *c, const Plan &p, const void *Q, void *O, 
   if ((int64_t)c->cfg.num_kv_heads * num_seqs * p.num_parts > INT32_MAX) return hipErrorInvalidValue;
   dim3 grid((unsigned)(c->cfg.num_kv_heads * num_seqs * p.num_parts)), block(WAVES * 64);
   const int lpt = p.lpt ? 1 : 0;
-  if (p.prefetch)
-    hipLaunchKernelGGL((paged_decode_mfma_kernel<G, WAVES, true>), grid, block, 0, s, (const uint16_t *)Q,
-                       (uint16_t *)O, c->pool, bt, max_blocks, cl, c->cfg.num_q_heads, c->block_bytes, (int)c->cfg.num_pool_blocks, c->scale,
-                       p.partition, p.num_parts, num_seqs, lpt, ws);
-  else
-    hipLaunchKernelGGL((paged_decode_mfma_kernel<G, WAVES, false>), grid, block, 0, s, (const uint16_t *)Q,
-                       (uint16_t *)O, c->pool, bt, max_blocks, cl, c->cfg.num_q_heads, c->block_bytes, (int)c->cfg.num_pool_blocks, c->scale,
-                       p.partition, p.num_parts, num_seqs, lpt, ws);
+  hipLaunchKernelGGL((paged_decode_mfma_kernel<G, WAVES>), grid, block, 0, s, (const uint16_t *)Q,
+                     (uint16_t *)O, c->pool, bt, max_blocks, cl, c->cfg.num_q_heads, c->block_bytes,
+                     (int)c->cfg.num_pool_blocks, c->scale, p.partition, p.num_parts, num_seqs, lpt, ws);
   return hipGetLastError();
 }
 
@@ -683,13 +656,10 @@ hipError_t launch_t(const lkv_ctx *c, const void *Q, void *O, const int32_t *bt,
   Workspace ws{wsbuf, wsbuf + (int64_t)num_seqs * Hq * p.num_parts * 2};
   hipError_t e;
   if (p.mfma && sizeof(T) == 2 && D == 128) {  // make_plan sets mfma only for this case
-    if (p.waves == 1) e = launch_mfma<G, 1>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
-    else if (p.waves == 2) e = launch_mfma<G, 2>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
-    else if (p.waves == 4) e = launch_mfma<G, 4>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
-    else e = launch_mfma<G, 8>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
-  } else if (p.waves <= 4) e = launch_w<T, D, G, 4>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
-  else if (p.waves == 8) e = launch_w<T, D, G, 8>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
-  else e = launch_w<T, D, G, 16>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
+    e = launch_mfma<G, 8>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
+  } else {
+    e = launch_w<T, D, G, 4>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
+  }
   if (e != hipSuccess || p.num_parts == 1) return e;
   hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(num_seqs * Hq), dim3(D), 0, s, (T *)O, cl, Hq, p.partition,
                      p.num_parts, ws);
