@@ -231,7 +231,8 @@ lkv_status lkv_write_kv(lkv_ctx *ctx, int32_t layer, const void *K, const void *
  * [T][num_q_heads][head_dim]; K, V: device, [T][num_kv_heads][head_dim]; cu_seqlens: device,
  * int32[num_seqs+1], sequence s is tokens cu[s]..cu[s+1].  Row i of a sequence sees keys
  * 0..i if causal != 0, all keys otherwise.  max_seqlen >= the longest sequence (sizes the
- * grid).  total_tokens = T (host-known, = cu[num_seqs]).  `layer` selects no data; it names
+ * grid).  total_tokens = T (host-known, = cu[num_seqs]; the launch is sized from it and from max_seqlen: with
+ * values smaller than the batch's, rows of O stay unwritten).  `layer` selects no data; it names
  * the layer whose compute this is, for the statistics.  bf16: fp32 accumulation, probabilities
  * rounded to bf16 before the value product; f32: fp32 throughout. */
 lkv_status lkv_prefill_attention(lkv_ctx *ctx, int32_t layer, const void *Q, const void *K, const void *V,

@@ -486,7 +486,7 @@ lkv_status lkv_prefill_attention(lkv_ctx *c, int32_t layer, const void *Q, const
     return fail(c, LKV_ERR_INVALID_ARG, "lkv_prefill_attention: tensors must be 16-byte aligned");
   hipEvent_t t0;
   if (lkv_status st = timed_begin(c, (hipStream_t)stream, &t0)) return st;
-  LKV_HIP(c, lkv::launch_prefill(c, Q, K, V, O, cu_seqlens, num_seqs, max_seqlen, causal, (hipStream_t)stream));
+  LKV_HIP(c, lkv::launch_prefill(c, Q, K, V, O, cu_seqlens, num_seqs, max_seqlen, total_tokens, causal, (hipStream_t)stream));
   if (lkv_status st = timed_end(c, (hipStream_t)stream, t0, 0, lkv_ctx::kTimedPrefill)) return st;
   c->stats.prefill_calls += 1;
   return LKV_OK;

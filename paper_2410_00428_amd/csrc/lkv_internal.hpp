@@ -108,8 +108,8 @@ hipError_t launch_paged_decode(const lkv_ctx *c, const void *Q, void *O, const i
 bool decode_supported(const lkv_ctx *c);
 
 hipError_t launch_prefill(const lkv_ctx *c, const void *Q, const void *K, const void *V, void *O,
-                          const int32_t *cu_seqlens, int32_t num_seqs, int32_t max_seqlen, int32_t causal,
-                          hipStream_t s);
+                          const int32_t *cu_seqlens, int32_t num_seqs, int32_t max_seqlen, int64_t total_tokens,
+                          int32_t causal, hipStream_t s);
 bool prefill_supported(const lkv_ctx *c);
 
 // Sustained bf16 MFMA rate and shader clock of the current device (measurement helper).

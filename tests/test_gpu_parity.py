@@ -196,6 +196,21 @@ def test_bf16_prefill_unit_and_tile_boundaries(causal):
     sc.close()
 
 
+@pytest.mark.parametrize("causal", [True, False])
+def test_bf16_prefill_mixed_batch_with_work_slots_from_the_total_token_count(causal):
+    """With the number of kv heads a multiple of 8 the d=128 kernel sizes its grid from the batch's total token
+    count and every workgroup finds its (sequence, tile pair) in cu_seqlens: more than 64 sequences (two rounds of
+    the search), lengths around the 256-token slot, one long sequence among many short ones, GQA."""
+    shape = wl.KVShape(1, 16, 8, 128, 16, "bf16")
+    rng = np.random.default_rng(16)
+    lens = [int(x) for x in rng.integers(1, 90, size=66)] + [255, 256, 257, 511, 513, 1300, 3]
+    order = rng.permutation(len(lens))
+    lens = tuple(lens[i] for i in order)
+    sc = Scenario(16, shape, lens, sum((n + 15) // 16 for n in lens) + 8)
+    sc.prefill_layer(0, causal=causal)
+    sc.close()
+
+
 def test_f32_head_dim_128_and_gqa():
     shape = wl.KVShape(1, 8, 2, 128, 16, "f32")
     sc = Scenario(14, shape, (100, 33), 32)
