@@ -28,7 +28,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
 # HBM bytes per launch of the dominant kernel (prefill_bf16_d128_kernel) from two rocprofv3 --pmc runs of this
 # command (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for the pack gather
 # kernel, which moves a known 256 MiB each way: see profiles/bench_workload2_hbm_traffic.md
-TRAFFIC_BYTES = {2: 512.7 * 2**20 + 128.0 * 2**20}
+TRAFFIC_BYTES = {2: 513.4 * 2**20 + 128.0 * 2**20}
 METRIC = "decode paged-attn HBM GB/s; prefill attn TFLOP/s; layer offload/reload GB/s"
 
 
