@@ -595,7 +595,7 @@ decode_combine_kernel(T *__restrict__ O, const int32_t *__restrict__ context_len
 // and with the partition fastest a short last partition (e.g. 2049 = 2048 + 1 tokens) would put all
 // the heavy workgroups on half of the XCDs.
 struct Plan {
-  int partition, num_parts;
+  int partition, num_parts, waves;
   bool mfma;
   bool lpt;  // workgroups take the launch's (sequence, partition) items longest first (see decode_work_item)
 };
@@ -603,12 +603,15 @@ struct Plan {
 Plan make_plan(const lkv_ctx *c, int num_seqs, int max_blocks) {
   const int64_t tokens = (int64_t)max_blocks * kBlock;
   const int64_t units = (int64_t)num_seqs * c->cfg.num_kv_heads;
-  Plan p{0, 1, false, false};
+  Plan p{0, 1, 4, false, false};
   p.mfma = c->cfg.dtype == LKV_BF16 && c->cfg.head_dim == 128;
   if (p.mfma) {
-    // measured on MI355X over the four decode workloads: 8 wavefronts per workgroup, two block pairs in
-    // flight per wavefront, partitions of 4096 tokens (contexts up to 4096 are not split at all)
+    // Measured on MI355X (sweep of partition 256..4096 x 2/4/8 wavefronts over batches of 1..256 sequences, contexts
+    // of 200..16384 tokens, MHA and 8-fold GQA): partitions of 4096 tokens when the batch alone fills the chip
+    // (contexts up to 4096 are then not split at all), halved until the launch has at least 128 workgroups (one
+    // 16384-token GQA sequence: 52 -> 28 us; one 2048-token MHA sequence: 26 -> 15 us).
     p.partition = 4096;
+    while (p.partition > 256 && units * ((tokens + p.partition - 1) / p.partition) < 128) p.partition >>= 1;
   } else {
     p.partition = 512;
     while (p.partition > 128 && units * ((tokens + p.partition - 1) / p.partition) < 2048) p.partition >>= 1;
@@ -616,6 +619,11 @@ Plan make_plan(const lkv_ctx *c, int num_seqs, int max_blocks) {
   if (c->cfg.decode_partition > 0) p.partition = c->cfg.decode_partition;
   p.num_parts = (int)((tokens + p.partition - 1) / p.partition);
   if (p.num_parts < 1) p.num_parts = 1;
+  // eight wavefronts share a workgroup's keys, except for many short items: with 512 or more workgroups of at most
+  // 1024 tokens each, two-wavefront workgroups (four resident per CU) lose less to start-up and the wave merge
+  // (256 contexts of 200 tokens: 218 -> 162 us; long items stream better with eight: ragged 16-sequence GQA batch
+  // 5.2 vs 4.3 TB/s)
+  if (p.mfma) p.waves = (units * p.num_parts >= 512 && (tokens < p.partition ? tokens : p.partition) <= 1024) ? 2 : 8;
   // Longest-first order pays when the launch is only a few rounds of workgroups deep: measured on a ragged
   // 16-sequence GQA batch +26%; with thousands of workgroups the tail is short anyway and the per-workgroup
   // search of the work list costs 2-4%.
@@ -656,7 +664,8 @@ hipError_t launch_t(const lkv_ctx *c, const void *Q, void *O, const int32_t *bt,
   Workspace ws{wsbuf, wsbuf + (int64_t)num_seqs * Hq * p.num_parts * 2};
   hipError_t e;
   if (p.mfma && sizeof(T) == 2 && D == 128) {  // make_plan sets mfma only for this case
-    e = launch_mfma<G, 8>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
+    e = p.waves == 2 ? launch_mfma<G, 2>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s)
+                     : launch_mfma<G, 8>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
   } else {
     e = launch_w<T, D, G, 4>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
   }

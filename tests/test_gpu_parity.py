@@ -259,6 +259,18 @@ def test_decode_ragged_batches_longest_first_work_list(B, Hq, Hkv, max_len):
     sc.close()
 
 
+@pytest.mark.parametrize("Hq,Hkv,lens", [(8, 2, (3000, 1111)), (8, 1, (2500,)), (4, 4, (600, 90, 1))])
+def test_decode_small_batches_get_smaller_partitions_from_the_plan(Hq, Hkv, lens):
+    """With the library's own plan (no partition given) a launch of a few sequences is cut into partitions of as
+    little as 256 tokens so that it still fills the chip; results must not depend on that."""
+    shape = wl.KVShape(1, Hq, Hkv, 128, 16, "bf16")
+    sc = Scenario(19, shape, lens, sum((n + 16) // 16 + 1 for n in lens) + 8)
+    sc.prefill_layer(0, check_attn=False)
+    sc.decode_step(0)
+    sc.decode_step(0, step=1)
+    sc.close()
+
+
 def test_decode_zero_context_and_poisoned_unused_slots():
     """context 0 gives a zero row; NaN in unused slots (tail of the last block, stale blocks) must not leak."""
     shape = wl.KVShape(1, 4, 2, 128, 16, "bf16")
