@@ -47,13 +47,6 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
   return __builtin_bit_cast(unsigned, v);
 }
 
-// Which (sequence, query head) pair XCD x takes as its lp-th.  The kv groups (the G query heads that share a kv
-// head, consecutive pairs) are dealt round-robin to the XCDs: all tiles of a group stay on one XCD's L2, and a batch
-// of unequal sequences loads every XCD alike (contiguous ranges would give one long sequence to a single XCD).
-__device__ __forceinline__ int xcd_pair(int x, int lp, int G, int pairs) {
-  const int pair = ((lp / G) * kXcds + x) * G + lp % G;
-  return pair < pairs ? pair : -1;
-}
 // Work slot k of a head -> (sequence, index of the tile pair inside it).  A sequence of n tokens owns ceil(n / 256)
 // consecutive slots (one per pair of 128-query tiles).  Up to 64 sequences are taken LONGEST FIRST (ties in batch
 // order), so that the long workgroups of an unequal batch start first and the short ones fill the end of the launch;
@@ -97,11 +90,6 @@ __device__ __forceinline__ bool find_pair_slot(const int32_t *__restrict__ cu_se
   }
   return false;
 }
-// pairs an XCD is given at most (host and device)
-__host__ __device__ __forceinline__ int64_t pairs_per_xcd(int64_t pairs, int G) {
-  return ((pairs / G + kXcds - 1) / kXcds) * G;
-}
-
 // QB blocks of 32 queries per wavefront (each K / V^T operand read from LDS feeds QB MFMAs; QB = 1 keeps
 // the kernel within 256 registers so that two workgroups share a CU and hide each other's latencies).
 // LDS is double-buffered: the next tile's global loads are issued before the current tile's math and
@@ -124,11 +112,11 @@ prefill_bf16_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__
   constexpr int VP = (VPATCHES + kThreads - 1) / kThreads;   // 4-key x 8-channel V patches per thread per tile
   __shared__ __attribute__((aligned(16))) char smem[SMEM];
 
-  // workgroup order: XCD (blockIdx.x % 8) -> its pairs in turn -> query tiles, longest first
-  const int li = blockIdx.x / kXcds;
-  const int qt = tiles_per_seq - 1 - li % tiles_per_seq;
-  const int rest = xcd_pair(blockIdx.x % kXcds, li / tiles_per_seq, Hq / Hkv, total_wgs / tiles_per_seq);
-  if (rest < 0) return;
+  // workgroup order: (sequence, head) pairs in turn, each with its query tiles longest first; consecutive
+  // workgroups go to consecutive XCDs, so the load is even whatever the head count
+  if ((int)blockIdx.x >= total_wgs) return;
+  const int qt = tiles_per_seq - 1 - blockIdx.x % tiles_per_seq;
+  const int rest = blockIdx.x / tiles_per_seq;
   const int h = rest % Hq, s = rest / Hq;
   const int t0 = cu_seqlens[s], n = cu_seqlens[s + 1] - t0;
   const int q0 = qt * BMQ;
@@ -391,38 +379,35 @@ template <bool CAUSAL>
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 prefill_bf16_d128_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
                          uint16_t *__restrict__ O, const int32_t *__restrict__ cu_seqlens, int Hq, int Hkv,
-                         int tiles_per_seq_max, int pairs, int num_seqs, int slots, float scale_log2e) {
+                         int num_seqs, int xcd_heads, float scale_log2e) {
   constexpr int D = 128, UK = 32, KR = 4, VR = 4, TB = UK * D * 2, VOFF = KR * TB;
   constexpr int BMQ = 128, WQ = 32, OS_STRIDE = D + 8;
   __shared__ __attribute__((aligned(1024))) char smem[(KR + VR) * TB];
 
   // Workgroup order.  A workgroup takes tile T-1-p and then tile p of a (sequence, head) pair: equal cost for all
-  // p of a sequence.  Two ways of dealing the work to the XCDs (blockIdx.x % 8), both keeping all tiles of a kv group
-  // on one XCD's L2:
-  //  * slots > 0 (the number of kv heads is a multiple of 8): XCD x owns kv heads x, x+8, ...; the grid holds, per
-  //    query head, `slots` work slots, an upper bound of the batch's tile pairs derived on the host from the total
-  //    token count, and find_pair_slot turns a slot into (sequence, p).  A batch of unequal sequences then launches
-  //    about as many workgroups as it has tile pairs, and each sequence pairs its own tiles.
-  //  * slots == 0: kv groups of (sequence, head) pairs are dealt round-robin (xcd_pair) and every sequence gets the
-  //    slots of the longest one; workgroups past a sequence's end leave at once.
+  // p of a sequence.  The grid holds, per query head, `slots` work slots, an upper bound of the batch's tile pairs
+  // derived on the host from the total token count; find_pair_slot turns a slot into (sequence, p), longest
+  // sequences first, so a batch of unequal sequences launches about as many workgroups as it has tile pairs and its
+  // long workgroups start first.  Slot-major order: all heads take slot 0, then slot 1, ...
+  //  * xcd_heads != 0 (the number of kv heads is a multiple of 8): XCD x (= blockIdx.x % 8) owns kv heads x, x+8,
+  //    ... of every sequence, so all tiles of a kv group share one L2 and every XCD is loaded alike.
+  //  * otherwise workgroup b is simply (slot b / Hq, head b % Hq): balanced for any head count (a tensor-parallel
+  //    slice may have one kv head), at the price of a head's K/V passing through several L2s.
   const int lane = threadIdx.x & 63;
-  const int xcd = blockIdx.x % kXcds, li = blockIdx.x / kXcds;
-  int h, s, pidx, tiles_per_seq;
-  if (slots > 0) {
-    // slot-major: the heads of an XCD take slot 0, then slot 1, ... (slot 0 is the longest sequence's)
+  int h, k;
+  if (xcd_heads) {
+    const int xcd = blockIdx.x % kXcds, li = blockIdx.x / kXcds;
     const int G = Hq / Hkv, hpx = Hq / kXcds, lhead = li % hpx;
     h = ((lhead / G) * kXcds + xcd) * G + lhead % G;
-    if (!find_pair_slot(cu_seqlens, num_seqs, li / hpx, lane, s, pidx)) return;
-    tiles_per_seq = 0;  // set from the sequence's own length below
+    k = li / hpx;
   } else {
-    const int halves = (tiles_per_seq_max + 1) / 2;
-    const int pair = xcd_pair(xcd, li / halves, Hq / Hkv, pairs);
-    if (pair < 0) return;
-    h = pair % Hq, s = pair / Hq, pidx = li % halves;
-    tiles_per_seq = tiles_per_seq_max;
+    h = blockIdx.x % Hq;
+    k = blockIdx.x / Hq;
   }
+  int s, pidx;
+  if (!find_pair_slot(cu_seqlens, num_seqs, k, lane, s, pidx)) return;
   const int t0 = cu_seqlens[s], n = cu_seqlens[s + 1] - t0;
-  if (slots > 0) tiles_per_seq = (n + BMQ - 1) / BMQ;
+  const int tiles_per_seq = (n + BMQ - 1) / BMQ;
 
   const int tid = threadIdx.x, ql = lane & 31, hh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -763,28 +748,21 @@ hipError_t launch_bf16_d128(const lkv_ctx *c, const void *Q, const void *K, cons
   if ((int64_t)max_seqlen * c->cfg.num_kv_heads * D * 2 >= ((int64_t)1 << 32)) return hipErrorInvalidValue;
   const int Hq = c->cfg.num_q_heads, Hkv = c->cfg.num_kv_heads;
   const int tiles = (max_seqlen + BMQ - 1) / BMQ, halves = (tiles + 1) / 2;
-  const int64_t pairs = (int64_t)Hq * num_seqs;
   // Work slots per head: the sum over the sequences of ceil(n / 256) is at most (T + 255 * num_seqs) / 256, and never
   // more than every sequence being as long as the longest.
-  int64_t slots = 0, grid_wgs;
-  if (Hkv % kXcds == 0) {
-    slots = (total_tokens + (int64_t)255 * num_seqs) / 256;
-    if (slots > (int64_t)halves * num_seqs) slots = (int64_t)halves * num_seqs;
-    grid_wgs = slots * Hq;  // Hq / 8 heads on each of the 8 XCDs
-  } else {
-    grid_wgs = pairs_per_xcd(pairs, Hq / Hkv) * halves * kXcds;
-  }
-  if (grid_wgs > INT32_MAX || slots > INT32_MAX) return hipErrorInvalidValue;
+  int64_t slots = (total_tokens + (int64_t)255 * num_seqs) / 256;
+  if (slots > (int64_t)halves * num_seqs) slots = (int64_t)halves * num_seqs;
+  const int64_t grid_wgs = slots * Hq;
+  if (grid_wgs > INT32_MAX) return hipErrorInvalidValue;
+  const int xcd_heads = Hkv % kXcds == 0;
   const float sl2 = c->scale * kLog2e;
   dim3 grid((unsigned)grid_wgs);
   if (causal)
     hipLaunchKernelGGL((prefill_bf16_d128_kernel<true>), grid, dim3(kThreads), 0, s, (const uint16_t *)Q,
-                       (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, cu, Hq, Hkv, tiles, (int)pairs, num_seqs,
-                       (int)slots, sl2);
+                       (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, cu, Hq, Hkv, num_seqs, xcd_heads, sl2);
   else
     hipLaunchKernelGGL((prefill_bf16_d128_kernel<false>), grid, dim3(kThreads), 0, s, (const uint16_t *)Q,
-                       (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, cu, Hq, Hkv, tiles, (int)pairs, num_seqs,
-                       (int)slots, sl2);
+                       (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, cu, Hq, Hkv, num_seqs, xcd_heads, sl2);
   return hipGetLastError();
 }
 
@@ -795,11 +773,10 @@ hipError_t launch_bf16(const lkv_ctx *c, const void *Q, const void *K, const voi
   // the kernel addresses a sequence's K/V rows with 32-bit byte offsets
   if ((int64_t)max_seqlen * c->cfg.num_kv_heads * D * 2 >= ((int64_t)1 << 32)) return hipErrorInvalidValue;
   const int tiles = (max_seqlen + BMQ - 1) / BMQ;
-  const int64_t pairs = (int64_t)c->cfg.num_q_heads * num_seqs, total = pairs * tiles;
-  const int64_t grid_wgs = pairs_per_xcd(pairs, c->cfg.num_q_heads / c->cfg.num_kv_heads) * tiles * kXcds;
-  if (grid_wgs > INT32_MAX) return hipErrorInvalidValue;
+  const int64_t total = (int64_t)c->cfg.num_q_heads * num_seqs * tiles;
+  if (total > INT32_MAX) return hipErrorInvalidValue;
   const float sl2 = c->scale * kLog2e;
-  dim3 grid((unsigned)grid_wgs);
+  dim3 grid((unsigned)total);
   if (causal)
     hipLaunchKernelGGL((prefill_bf16_kernel<D, true, QB>), grid, dim3(kThreads), 0, s, (const uint16_t *)Q,
                        (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, cu, c->cfg.num_q_heads,
