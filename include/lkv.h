@@ -14,7 +14,14 @@
  *     attention (Section 2.1.1), a layer's blocks are packed and copied to pinned host memory
  *     on a side stream while compute continues and copied back layer by layer for decoding
  *     (Sections 3.2.1 and 4), and decoding attends through the layer's block table
- *     (Sections 2.1.2, 2.2: paged attention over non-contiguous blocks).
+ *     (Sections 2.1.2, 2.2: paged attention over non-contiguous blocks);
+ *   - the same images can live in ordinary host memory behind a small ring of pinned transfer
+ *     units drained by CPU threads (Section 4), each unit passing a caller-given link check
+ *     (Section 3.2.3);
+ *   - the host-side policy of the method as pure functions: the prefill and offload cost
+ *     models and the number of layers to retain (Sections 3.1, 3.2.1), the SLO-aware admission
+ *     of queued prefills (Section 3.1, Algorithm 1), the free-block forecast and the pressure
+ *     rule (Section 3.2.1).
  *
  * Conventions
  *   Pointers  "device" = memory of the current HIP device; "host" = ordinary host memory,

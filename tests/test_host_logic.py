@@ -211,3 +211,20 @@ def test_tier_and_gate_calls_validate_arguments_without_a_device():
     assert e.value.status == lkv.LKV_ERR_INVALID_ARG
     c.set_link_gate(lambda: False, delay_us=0, max_checks=3)   # host state only: allowed
     c.set_link_gate(None)
+
+
+def test_header_is_plain_c_and_the_library_links_and_runs_from_c(tmp_path):
+    """include/lkv.h compiles as pedantic C99, and a C program linked against liblkv.so runs the device-free part
+    of the ABI (logical context, layer plan, retention driver) to the documented results."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no host compiler")
+    exe = str(tmp_path / "c_abi_check")
+    libdir = os.path.dirname(lkv.LIB_PATH)
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                        os.path.join(ROOT, "tests", "native", "c_abi_check.c"), "-o", exe, "-L", libdir, "-llkv",
+                        "-Wl,-rpath," + libdir], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and "c_abi_check: ok" in r.stdout, r.stdout + r.stderr
