@@ -45,7 +45,9 @@ class LayerKVEngine:
         self.lens = []
 
     def _timed(self, name: str, stream, fn):
-        if not self.timing:
+        """timing: False = no events from here; "side" = only around the side-stream transfers (their spans cannot
+        be had otherwise); True = around every call (each pair of events also delays the launch it brackets)."""
+        if not self.timing or (self.timing == "side" and stream is self.main):
             return fn()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record(stream)
