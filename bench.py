@@ -188,7 +188,9 @@ def main():
     prefill_tflops = pf_flops / (prefill_ms_lib * 1e-3) / 1e12
     prefill_tflops_py = pf_flops / (avg("prefill_attention") * 1e-3) / 1e12
     # write_kv is called for the prompts (T tokens) and for every decode step (B tokens); only the former count
-    write_gbs = 2 * T * sh.token_bytes / (avg("write_kv") * 1e-3) / 1e9
+    write_gbs = stats["write_kernel_bytes"] / max(stats["write_kernel_ns"], 1)     # library events; includes the
+    # few-microsecond launches that append the decode step's tokens (about 5 % of the time, none of the bytes)
+    write_gbs_py = 2 * T * sh.token_bytes / (avg("write_kv") * 1e-3) / 1e9
     pack_gbs = stats["pack_kernel_bytes"] / max(stats["pack_kernel_ns"], 1)      # bytes/ns = GB/s
     unpack_gbs = stats["unpack_kernel_bytes"] / max(stats["unpack_kernel_ns"], 1)
 
@@ -374,7 +376,16 @@ def main():
     bt_rows, bt_w = [bt_all[l] for l in range(L)], bt_all.shape[2]
     t_decode = alone(lambda: [c.paged_decode_attention(l, dq[l], dO, bt_rows[l], bt_w, cl_dev, B, eng.main)
                               for l in range(L)], L, reps=5)
-    iso["write_kv_GBps"] = 2 * T * sh.token_bytes / (t_write * 1e-3) / 1e9
+    iso["write_kv_GBps_back_to_back_from_python"] = 2 * T * sh.token_bytes / (t_write * 1e-3) / 1e9
+    # an 80 us kernel launched from Python is partly launch-bound; the kernel itself, by the library's events:
+    c.set_profiling(True)
+    w0 = c.get_stats()
+    for l in range(L):
+        c.write_kv(l, Ks[l % n_in], Vs[l % n_in], slot_rows[l], T, eng.main)
+    w1 = c.get_stats()
+    c.set_profiling(False)
+    iso["write_kv_GBps"] = (w1["write_kernel_bytes"] - w0["write_kernel_bytes"]) / max(
+        w1["write_kernel_ns"] - w0["write_kernel_ns"], 1)
     iso["prefill_attn_TFLOPs"] = pf_flops / (t_prefill * 1e-3) / 1e12
     iso["decode_paged_attn_GBps"] = decode_bytes_per_launch[0] / (t_decode * 1e-3) / 1e9
     iso = {k: (round(v, 2) if isinstance(v, float) else v) for k, v in iso.items()}
@@ -407,7 +418,8 @@ def main():
             "prefill_ms_per_layer_no_copy_running": round(sum(pf_quiet) / max(len(pf_quiet), 1), 4),
             "prefill_ms_per_layer_copy_running": round(sum(pf_overlap) / max(len(pf_overlap), 1), 4),
             "write_kv_GBps": round(write_gbs, 2),
-            "write_kv_us_per_layer": round(avg("write_kv") * 1e3, 2),
+            "write_kv_GBps_events_from_python": round(write_gbs_py, 2),
+            "write_kv_us_per_layer_events_from_python": round(avg("write_kv") * 1e3, 2),
             "pack_kernel_GBps": round(pack_gbs, 2), "unpack_kernel_GBps": round(unpack_gbs, 2),
             "offload_GBps": None if off_gbs is None else round(off_gbs, 2),
             "reload_GBps": None if rel_gbs is None else round(rel_gbs, 2),

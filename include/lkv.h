@@ -127,6 +127,8 @@ typedef struct {
   int64_t tier_copy_bytes, tier_copy_ns;
   int64_t ring_wait_ns;
   int64_t gate_busy_answers;
+  /* bytes (read + write) moved by the lkv_write_kv launches counted in write_kernel_ns */
+  int64_t write_kernel_bytes;
 } lkv_stats;
 
 /* ------------------------------------------------------------------ life cycle */

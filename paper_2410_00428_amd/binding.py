@@ -55,7 +55,7 @@ class LkvStats(ctypes.Structure):
                  "unpack_kernel_bytes", "write_kernel_ns", "write_kernel_launches", "prefill_kernel_ns",
                  "prefill_kernel_launches", "decode_kernel_ns", "decode_kernel_launches",
                  "pageable_offload_calls", "pageable_offload_bytes", "pageable_reload_calls", "pageable_reload_bytes",
-                 "tier_copy_bytes", "tier_copy_ns", "ring_wait_ns", "gate_busy_answers")]
+                 "tier_copy_bytes", "tier_copy_ns", "ring_wait_ns", "gate_busy_answers", "write_kernel_bytes")]
 
 
 LINK_BUSY_FN = ctypes.CFUNCTYPE(ctypes.c_int32, ctypes.c_void_p)

@@ -780,6 +780,7 @@ lkv_status lkv_get_stats(lkv_ctx *c, lkv_stats *out, int64_t size) {
       case lkv_ctx::kTimedWrite:
         c->stats.write_kernel_ns += ns;
         c->stats.write_kernel_launches += 1;
+        c->stats.write_kernel_bytes += t.bytes;
         break;
       case lkv_ctx::kTimedPrefill:
         c->stats.prefill_kernel_ns += ns;
