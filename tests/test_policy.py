@@ -233,3 +233,74 @@ def test_gated_units_closed_forms():
     assert po.gated_units([True, True, False, True, False], 3, 5) == (6, 3)
     assert po.gated_units([True] * 9, 4, 0) == (0, 0)   # no question allowed: ungated
     assert po.gated_units([], 0, 5) == (0, 0)
+
+
+def test_scheduler_on_a_simulated_request_trace():
+    """Section 3.1 end to end on a seeded trace (the trained length predictor is replaced by a bucket stub that
+    knows the true output length): at every scheduling event the library admits exactly as many queued prefills
+    as the oracle, and the number admitted means what Eq. 1-2 say - with it every decoding request still meets its
+    TPOT target on the projection the paper uses, with one more at least one would not.  All times are multiples of
+    2^-20 s, so the library's doubles and the oracle's rationals see the same numbers."""
+    rng = random.Random(31)
+    U = F(1, 2**20)
+
+    def t_prefill(s):                      # Eq. 3 with dyadic coefficients: s * (a + b s)
+        return s * (256 + s // 8) * U      # 1024 tokens: 0.25 s + 0.125 s
+
+    dt_decode = 16384 * U                   # one decoding iteration: 1/64 s
+    t_tpot = 131072 * U                     # target: 8 iterations per token
+    reqs, t = [], F(0)
+    for i in range(60):
+        t += rng.randint(1, 150000) * U
+        out_len = rng.randint(8, 200)
+        reqs.append(dict(arrival=t, prompt=rng.choice((64, 256, 512, 1024)), out=out_len,
+                         lower=out_len - out_len % 32, n_past=0, done=False, ttft=None))
+    pending, queue, running = list(range(60)), [], []
+    now, events, binding_events, mixed_events = F(0), 0, 0, 0
+    while pending or queue or running:
+        events += 1
+        assert events < 100000
+        while pending and reqs[pending[0]]["arrival"] <= now:
+            queue.append(pending.pop(0))
+        if not queue and not running:
+            now = reqs[pending[0]]["arrival"]
+            continue
+        dec = [dict(t_tpot=float(t_tpot), n_past=reqs[i]["n_past"], t_past=float(now - reqs[i]["arrival"]),
+                    predicted_lower_bound=reqs[i]["lower"]) for i in running]
+        tq = [t_prefill(reqs[i]["prompt"]) for i in queue]
+        n_lib = lkv.max_prefills(dec, [float(x) for x in tq])
+        allow = [po.allow_prefill_time(t_tpot, d["n_past"], now - reqs[i]["arrival"], d["predicted_lower_bound"])
+                 for d, i in zip(dec, running)]
+        assert n_lib == po.max_prefills(allow, tq), f"event {events}"
+        # what n means, from the definitions: mean TPOT projected over all tokens after a delay D is
+        # (T_past + D + T_future) / (N_past + N_future) with T_future = current pace * N_future
+        def projected_ok(delay):
+            for i in running:
+                r = reqs[i]
+                n_fut = max(1, r["lower"] - r["n_past"])
+                t_past = now - r["arrival"]
+                pace = t_past / r["n_past"] if r["n_past"] else t_tpot
+                if not (t_past + delay + pace * n_fut) < t_tpot * (r["n_past"] + n_fut):
+                    return False
+            return True
+        assert n_lib == 0 or projected_ok(sum(tq[:n_lib]))
+        if n_lib < len(queue):
+            assert not projected_ok(sum(tq[:n_lib + 1]))
+            binding_events += 1
+        if running and 0 < n_lib:
+            mixed_events += 1
+        if n_lib > 0:                                   # a prefill batch: its requests produce their first token
+            now += sum(tq[:n_lib])
+            for i in queue[:n_lib]:
+                reqs[i]["n_past"], reqs[i]["ttft"] = 1, now - reqs[i]["arrival"]
+                running.append(i)
+            queue = queue[n_lib:]
+        else:                                           # one decoding iteration of everything that runs
+            now += dt_decode
+            for i in running:
+                reqs[i]["n_past"] += 1
+        for i in [i for i in running if reqs[i]["n_past"] >= reqs[i]["out"]]:
+            reqs[i]["done"] = True
+            running.remove(i)
+    assert all(r["done"] and r["ttft"] is not None for r in reqs)
+    assert binding_events > 10 and mixed_events > 10      # the constraint bound, and prefills ran next to decoders
