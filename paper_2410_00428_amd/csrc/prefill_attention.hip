@@ -476,7 +476,8 @@ prefill_bf16_d128_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restr
     }
     const int kv_end = CAUSAL ? min(n, q0 + BMQ) : n;
     const int nunits = (kv_end + UK - 1) / UK;
-    const int last_w = CAUSAL ? min(nunits - 1, wq0 / UK) : nunits - 1;  // last unit this wavefront needs
+    // last unit this wavefront needs; none at all when its 32 rows lie past the end of the sequence
+    const int last_w = wq0 >= n ? -1 : CAUSAL ? min(nunits - 1, wq0 / UK) : nunits - 1;
 
     // rows past the end of the sequence are fetched as copies of the last row (their scores are masked)
     auto issue = [&](const __amdgpu_buffer_rsrc_t &rsrc, const unsigned (&off)[2], int t, unsigned ring_base, bool is_k) {
