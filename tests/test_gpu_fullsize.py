@@ -281,3 +281,25 @@ def test_workload5_mixed_batch_reload_on_side_stream_while_decoding():
         c.event_synchronize(layer, lkv.LKV_EV_OFFLOADED)
         assert buf.numpy()[:ref.nbytes].tobytes() == ref.tobytes(), f"offload image of the new prompts, layer {layer}"
     c.destroy()
+
+
+# ----------------------------------------------------------------------------- mixed-length prefill batch
+def test_mixed_length_prefill_batch_at_the_7b_head_count_sampled_rows():
+    """The paper's traffic mixes prompt lengths (Section 5.1); a batch of one long prompt among short ones is what
+    the slot grid of the d=128 kernel is for (work slots from the total token count, sequences longest first, kv
+    heads dealt to the XCDs).  Sampled causal rows of every sequence, including every row of the shortest."""
+    sh = wl.SHAPE_7B
+    lens = [257, 8192, 64, 1300, 1, 511, 3000, 128, 129, 700]
+    T = sum(lens)
+    Q, K, V = wl.qkv(5, 3, T, sh, 128 ** -0.5)
+    c = lkv.LKV(1, sh.num_q_heads, sh.num_kv_heads, sh.head_dim, 16, 64, "bf16")
+    Od = H.empty_like_storage(Q.shape, "bf16")
+    Od.fill_(0x7FC0)   # every row must be overwritten
+    c.prefill_attention(0, H.to_dev(Q), H.to_dev(K), H.to_dev(V), Od, H.to_dev(wl.cu_seqlens(lens)), len(lens),
+                        max(lens), T, True)
+    torch.cuda.synchronize()
+    got = H.to_host(Od, "bf16")
+    assert not np.isnan(got).any(), "a row of O was not written"
+    pairs = [(s, h) for s in range(len(lens)) for h in ((3 * s) % 32, 31 - s)]
+    sampled_prefill_check(5, 3, Q, K, V, Od, lens, sh, 128 ** -0.5, pairs, rows_per=24)
+    c.destroy()
