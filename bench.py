@@ -94,6 +94,53 @@ def cpu_baseline(w, seconds: float) -> dict:
             "prefill_sample": f"{len(tok)} sampled causal rows of one {n0}-token prompt"}
 
 
+def decode_other_workloads(torch, dev) -> dict:
+    """Paged decode attention of the other configurations' decode batches (not bench lines: context for the
+    headline figure).  A few layers of the workload's KV, blocks handed out in a seeded random order over the pool,
+    the layers taken in turn so that nothing stays in the last-level cache; kernel time from the library's events."""
+    from paper_2410_00428_amd import binding as lkv_b
+    from paper_2410_00428_amd import workloads as wl
+    out = {}
+    for number, layers in ((3, 8), (4, 16), (5, 2)):
+        w = wl.workload(number)
+        sh = w.shape
+        lens = [n + 1 for n in w.prompt_lens] if number == 3 else list(w.decode_lens)
+        B = len(lens)
+        nblk = sum(wl.blocks_for(n, sh.block_size) for n in lens) * layers
+        pool = (torch.randn(nblk * sh.block_bytes // 2, device=dev, dtype=torch.float32) * w.data_scale).to(torch.bfloat16)
+        c = lkv_b.LKV(layers, sh.num_q_heads, sh.num_kv_heads, sh.head_dim, sh.block_size, nblk, "bf16", pool=pool)
+        c.pool_reset(wl.free_list_order(number, nblk, index=55))
+        tables = []
+        for l in range(layers):
+            for s_, n in enumerate(lens):
+                c.alloc_layer_blocks(s_, l, n)
+            tables.append(torch.from_numpy(c.padded_block_table(range(B), l)).to(dev))
+        cl = torch.tensor(lens, dtype=torch.int32, device=dev)
+        q = (torch.randn(B, sh.num_q_heads, sh.head_dim, device=dev) * w.data_scale).to(torch.bfloat16)
+        o = torch.empty_like(q)
+        reps = 3
+
+        def sweep():
+            for l in range(layers):
+                c.paged_decode_attention(l, q, o, tables[l], tables[l].shape[1], cl, B)
+        sweep()
+        torch.cuda.synchronize()
+        c.set_profiling(True)
+        s0 = c.get_stats()
+        for _ in range(reps):
+            sweep()
+        s1 = c.get_stats()
+        c.set_profiling(False)
+        us = (s1["decode_kernel_ns"] - s0["decode_kernel_ns"]) / (reps * layers) * 1e-3
+        kv_bytes = sum(lens) * sh.token_bytes
+        out[str(number)] = {"workload": w.name, "seqs": B, "kv_MiB_per_layer": round(kv_bytes / 2**20, 1),
+                            "us_per_layer": round(us, 1), "GBps": round(kv_bytes / us / 1e3, 1),
+                            "frac_of_hbm_peak": round(kv_bytes / us / 1e3 / HBM_PEAK_GBS, 4)}
+        c.destroy()
+        del pool, tables
+    return out
+
+
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -395,6 +442,7 @@ def main():
     torch.cuda.synchronize()
     mf_rand = c.probe_mfma_rate(30.0, True, eng.main)
     mf_const = c.probe_mfma_rate(30.0, False, eng.main)
+    others = decode_other_workloads(torch, dev)
 
     out = {
         "metric": METRIC, "value": round(decode_gbs, 2), "unit": "GB/s",
@@ -454,6 +502,7 @@ def main():
             "unpack": {"bound": "hbm", "achieved": round(unpack_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                        "frac": round(unpack_gbs / HBM_PEAK_GBS, 4)},
         },
+        "decode_other_workloads": others,
     }
     eng.close()
     if not args.no_cpu_baseline:
