@@ -251,7 +251,10 @@ lkv_status lkv_prefill_attention(lkv_ctx *ctx, int32_t layer, const void *Q, con
 /* Offload image of one layer (Sections 3.2.1, 4): waits (on `stream`) for LKV_EV_KV_WRITTEN of
  * the layer, gathers blocks block_ids[0..n) (host array) into device staging and copies them to
  * pinned_dst (n*beta bytes), all on `stream`; records LKV_EV_PACKED after the last gather and
- * LKV_EV_OFFLOADED after the last copy.  Does not touch tables or the free list. */
+ * LKV_EV_OFFLOADED after the last copy.  Does not touch tables or the free list.  Host-link copies are paced:
+ * at most two per direction are queued at a time, so this call (and lkv_unpack_layer_blocks) blocks the calling
+ * thread until the copy two places ahead of its own has finished -- a caller that must keep launching compute
+ * meanwhile issues its transfers from a thread of their own (with its own context lock). */
 lkv_status lkv_pack_layer_blocks(lkv_ctx *ctx, int32_t layer, const int32_t *block_ids, int64_t n,
                                  void *pinned_dst, void *stream);
 /* Reload (Section 4: layer by layer, host to device): copies n*beta bytes from pinned_src into
