@@ -253,8 +253,8 @@ lkv_status lkv_prefill_attention(lkv_ctx *ctx, int32_t layer, const void *Q, con
  * pinned_dst (n*beta bytes), all on `stream`; records LKV_EV_PACKED after the last gather and
  * LKV_EV_OFFLOADED after the last copy.  Does not touch tables or the free list.  Host-link copies are paced:
  * at most two per direction are queued at a time, so this call (and lkv_unpack_layer_blocks) blocks the calling
- * thread until the copy two places ahead of its own has finished -- a caller that must keep launching compute
- * meanwhile issues its transfers from a thread of their own (with its own context lock). */
+ * thread until the copy two places ahead of its own has finished (at most the duration of one chunk's copy per
+ * chunk issued; staging_bytes sets the chunk size). */
 lkv_status lkv_pack_layer_blocks(lkv_ctx *ctx, int32_t layer, const int32_t *block_ids, int64_t n,
                                  void *pinned_dst, void *stream);
 /* Reload (Section 4: layer by layer, host to device): copies n*beta bytes from pinned_src into
