@@ -57,13 +57,17 @@ class LayerKVOracle:
     """Block pool, per-layer tables and residency; byte-exact write / pack / unpack."""
 
     def __init__(self, num_layers: int, num_q_heads: int, num_kv_heads: int, head_dim: int,
-                 block_size: int, num_pool_blocks: int, dtype: str):
-        assert dtype in ("f32", "bf16")
+                 block_size: int, num_pool_blocks: int, dtype: str, k_scale: float = 1.0, v_scale: float = 1.0):
+        # "fp8": the pool holds E4M3 codes (oracle/fp8_codec.py) of K / k_scale and V / v_scale; queries, the new
+        # keys and values handed to write_kv, and the outputs are bf16
+        assert dtype in ("f32", "bf16", "fp8")
         assert num_q_heads % num_kv_heads == 0
         self.L, self.Hq, self.Hkv, self.d, self.bs = num_layers, num_q_heads, num_kv_heads, head_dim, block_size
         self.num_pool_blocks = num_pool_blocks
         self.dtype = dtype
-        self.np_dtype = np.float32 if dtype == "f32" else np.uint16
+        self.np_dtype = {"f32": np.float32, "bf16": np.uint16, "fp8": np.uint8}[dtype]
+        self.in_dtype = np.float32 if dtype == "f32" else np.uint16       # what write_kv is given
+        self.k_scale, self.v_scale = float(k_scale), float(v_scale)
         # documented in-block order: [kv head][K then V][token in block][channel]
         self.pool = np.zeros((num_pool_blocks, num_kv_heads, 2, block_size, head_dim), dtype=self.np_dtype)
         self.free: List[int] = []          # a stack; the LAST element is handed out next
@@ -144,7 +148,10 @@ class LayerKVOracle:
     # ------------------------------------------------------------------ data movement
     def write_kv(self, K: np.ndarray, V: np.ndarray, slot_mapping: np.ndarray) -> None:
         """Token t's keys and values (all KV heads) go to slot ``slot_mapping[t]``; negative = skip."""
-        assert K.shape == V.shape and K.shape[1:] == (self.Hkv, self.d) and K.dtype == self.np_dtype
+        assert K.shape == V.shape and K.shape[1:] == (self.Hkv, self.d) and K.dtype == self.in_dtype
+        if self.dtype == "fp8":
+            from oracle import fp8_codec
+            K, V = fp8_codec.quantize_bf16_bits(K, self.k_scale), fp8_codec.quantize_bf16_bits(V, self.v_scale)
         for t in range(K.shape[0]):
             slot = int(slot_mapping[t])
             if slot < 0:
@@ -179,9 +186,19 @@ class LayerKVOracle:
 
     # ------------------------------------------------------------------ attention (C)
     def prefill_attention(self, Q, K, V, cu_seqlens, causal=True, scale=None, acc="f64", threads=1):
-        return prefill_attention(Q, K, V, cu_seqlens, self.dtype, causal, scale, acc, threads)
+        # prompts are attended in the precision they arrive in; the pool's format plays no part
+        return prefill_attention(Q, K, V, cu_seqlens, "bf16" if self.dtype == "fp8" else self.dtype, causal, scale,
+                                 acc, threads)
 
     def paged_decode_attention(self, Q, block_table, context_lens, scale=None, acc="f64", threads=1):
+        if self.dtype == "fp8":
+            # the stored values are code * scale: the codes' exact values go through the float32 path of the same
+            # routine, k_scale joins the softmax scale and v_scale multiplies the result
+            from oracle import fp8_codec
+            q32 = (np.ascontiguousarray(Q, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+            sm = (float(self.d) ** -0.5 if scale is None else float(scale)) * self.k_scale
+            return paged_decode_attention(q32, fp8_codec.decode(self.pool), block_table, context_lens, self.bs, "f32",
+                                          sm, acc, threads) * self.v_scale
         return paged_decode_attention(Q, self.pool, block_table, context_lens, self.bs, self.dtype,
                                       scale, acc, threads)
 
