@@ -141,6 +141,58 @@ def decode_other_workloads(torch, dev) -> dict:
     return out
 
 
+def fp8_pool_figures(torch, dev) -> dict:
+    """The 8-bit pool (E4M3 codes, the paper's future-work direction) on workload 2's shape: write of 16384 prompt
+    tokens per layer and decode attention over 8 x 2049 tokens, 16 layers taken in turn; bytes are the pool's."""
+    from paper_2410_00428_amd import binding as lkv_b
+    from paper_2410_00428_amd import workloads as wl
+    w = wl.workload(2)
+    sh = w.shape
+    layers, lens = 16, [n + 1 for n in w.prompt_lens]
+    B, T = len(lens), sum(w.prompt_lens)
+    nblk = sum(wl.blocks_for(n, sh.block_size) for n in lens) * layers
+    c = lkv_b.LKV(layers, sh.num_q_heads, sh.num_kv_heads, sh.head_dim, sh.block_size, nblk, "fp8",
+                  k_scale=w.data_scale / 16, v_scale=w.data_scale / 16)
+    c.pool_reset(wl.free_list_order(2, nblk, index=56))
+    slots, tables = [], []
+    for l in range(layers):
+        for s_, n in enumerate(lens):
+            c.alloc_layer_blocks(s_, l, n)
+        slots.append(torch.from_numpy(np.concatenate(
+            [c.build_slot_mapping(s_, l, 0, n - 1) for s_, n in enumerate(lens)])).to(dev))
+        tables.append(torch.from_numpy(c.padded_block_table(range(B), l)).to(dev))
+    K = [(torch.randn(T, sh.num_kv_heads, sh.head_dim, device=dev) * w.data_scale).to(torch.bfloat16) for _ in range(4)]
+    q = (torch.randn(B, sh.num_q_heads, sh.head_dim, device=dev) * w.data_scale).to(torch.bfloat16)
+    o = torch.empty_like(q)
+    cl = torch.tensor(lens, dtype=torch.int32, device=dev)
+
+    def sweep():
+        for l in range(layers):
+            c.write_kv(l, K[l % 4], K[(l + 1) % 4], slots[l], T)
+        for l in range(layers):
+            c.paged_decode_attention(l, q, o, tables[l], tables[l].shape[1], cl, B)
+    sweep()
+    torch.cuda.synchronize()
+    c.set_profiling(True)
+    s0 = c.get_stats()
+    for _ in range(3):
+        sweep()
+    s1 = c.get_stats()
+    c.set_profiling(False)
+    n_launch = 3 * layers
+    dec_us = (s1["decode_kernel_ns"] - s0["decode_kernel_ns"]) / n_launch * 1e-3
+    wr_us = (s1["write_kernel_ns"] - s0["write_kernel_ns"]) / n_launch * 1e-3
+    kv_bytes = sum(lens) * c.token_bytes
+    out = {"pool_bytes_per_token_per_layer": c.token_bytes,
+           "decode_us_per_layer": round(dec_us, 1), "decode_pool_GBps": round(kv_bytes / dec_us / 1e3, 1),
+           "decode_tokens_per_us": round(sum(lens) / dec_us, 1),
+           "write_us_per_layer": round(wr_us, 1),
+           "write_GBps_in_plus_out": round(T * (sh.num_kv_heads * sh.head_dim * 2 * 2 + c.token_bytes) / wr_us / 1e3, 1),
+           "note": "an offload image is half the bf16 one, so the link time of every offload and reload halves"}
+    c.destroy()
+    return out
+
+
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -443,6 +495,7 @@ def main():
     mf_rand = c.probe_mfma_rate(30.0, True, eng.main)
     mf_const = c.probe_mfma_rate(30.0, False, eng.main)
     others = decode_other_workloads(torch, dev)
+    fp8_fig = fp8_pool_figures(torch, dev)
 
     out = {
         "metric": METRIC, "value": round(decode_gbs, 2), "unit": "GB/s",
@@ -503,6 +556,7 @@ def main():
                        "frac": round(unpack_gbs / HBM_PEAK_GBS, 4)},
         },
         "decode_other_workloads": others,
+        "fp8_pool": fp8_fig,
     }
     eng.close()
     if not args.no_cpu_baseline:

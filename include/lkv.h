@@ -39,7 +39,7 @@
  *   Threads   a context is not thread-safe; use one thread per context or lock outside.
  *
  * Storage format of the pool (also the format of an offloaded image)
- *   e = element size (4 for LKV_F32, 2 for LKV_BF16), tau = 2*num_kv_heads*head_dim*e bytes
+ *   e = element size (4 for LKV_F32, 2 for LKV_BF16, 1 for LKV_FP8_E4M3), tau = 2*num_kv_heads*head_dim*e bytes
  *   per token per layer, beta = block_size*tau bytes per block.  Block b starts at byte
  *   b*beta.  Inside a block the order is [kv_head][K then V][token in block][channel]:
  *     K of token slot (b, o), head h, channel c:  b*beta + h*(2*block_size*head_dim*e)
@@ -69,7 +69,12 @@ typedef enum {
   LKV_ERR_UNSUPPORTED = 6   /* shape outside what the kernels are built for                    */
 } lkv_status;
 
-typedef enum { LKV_F32 = 0, LKV_BF16 = 1 } lkv_dtype;
+/* LKV_FP8_E4M3: the pool holds one-byte OCP E4M3 codes (1 sign, 4 exponent, 3 mantissa bits, bias 7, largest value
+ * 448, no infinities) of K / k_scale and V / v_scale; queries, the keys and values given to lkv_write_kv, prompts
+ * and outputs stay bf16.  The paper names KV-cache quantisation as the next step (its Future Work section) without
+ * fixing a format: this is this library's choice.  It halves tau, beta, every offload image and the bytes decode
+ * attention reads.  Attention kernels: head_dim 128 only. */
+typedef enum { LKV_F32 = 0, LKV_BF16 = 1, LKV_FP8_E4M3 = 2 } lkv_dtype;
 
 /* residency of one (request, layer), Section 3.2.2 */
 enum { LKV_RES_NONE = 0, LKV_RES_GPU = 1, LKV_RES_HOST = 2 };
@@ -99,6 +104,9 @@ typedef struct {
                                to let the library allocate (and free) it                       */
   int64_t staging_bytes;    /* device staging per transfer direction; 0 => 256 MiB.  A layer
                                image larger than this is moved in several chunks               */
+  float k_scale, v_scale;   /* LKV_FP8_E4M3 only: stored code = nearest E4M3 value (ties to even, saturating
+                               at +-448, NaN kept) of x * (1.0f / scale), the product rounded once to
+                               float; 0 => 1.0                                                   */
 } lkv_config;
 
 typedef struct {

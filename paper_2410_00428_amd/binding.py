@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(HERE, "liblkv.so")
 
 LKV_OK, LKV_ERR_INVALID_ARG, LKV_ERR_NO_BLOCKS, LKV_ERR_NOT_RESIDENT = 0, 1, 2, 3
 LKV_ERR_HOST_MEMORY, LKV_ERR_DEVICE, LKV_ERR_UNSUPPORTED = 4, 5, 6
-LKV_F32, LKV_BF16 = 0, 1
+LKV_F32, LKV_BF16, LKV_FP8_E4M3 = 0, 1, 2
 LKV_RES_NONE, LKV_RES_GPU, LKV_RES_HOST = 0, 1, 2
 LKV_EV_KV_WRITTEN, LKV_EV_PACKED, LKV_EV_OFFLOADED, LKV_EV_RELOADED = 0, 1, 2, 3
 STATUS_NAMES = {0: "LKV_OK", 1: "LKV_ERR_INVALID_ARG", 2: "LKV_ERR_NO_BLOCKS", 3: "LKV_ERR_NOT_RESIDENT",
@@ -45,7 +45,8 @@ class LkvConfig(ctypes.Structure):
     _fields_ = [("num_layers", ctypes.c_int32), ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("block_size", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("num_pool_blocks", ctypes.c_int64), ("softmax_scale", ctypes.c_float),
-                ("decode_partition", ctypes.c_int32), ("pool", ctypes.c_void_p), ("staging_bytes", ctypes.c_int64)]
+                ("decode_partition", ctypes.c_int32), ("pool", ctypes.c_void_p), ("staging_bytes", ctypes.c_int64),
+                ("k_scale", ctypes.c_float), ("v_scale", ctypes.c_float)]
 
 
 class LkvStats(ctypes.Structure):
@@ -239,11 +240,12 @@ class LKV:
 
     def __init__(self, num_layers: int, num_q_heads: int, num_kv_heads: int, head_dim: int, block_size: int,
                  num_pool_blocks: int, dtype: str, softmax_scale: float = 0.0, decode_partition: int = 0,
-                 pool=None, staging_bytes: int = 0, logical_only: bool = False):
+                 pool=None, staging_bytes: int = 0, logical_only: bool = False, k_scale: float = 0.0,
+                 v_scale: float = 0.0):
         self.lib = load_library()
         self.cfg = LkvConfig(num_layers, num_q_heads, num_kv_heads, head_dim, block_size,
-                             {"f32": LKV_F32, "bf16": LKV_BF16}[dtype], num_pool_blocks, softmax_scale,
-                             decode_partition, _ptr(pool), staging_bytes)
+                             {"f32": LKV_F32, "bf16": LKV_BF16, "fp8": LKV_FP8_E4M3}[dtype], num_pool_blocks,
+                             softmax_scale, decode_partition, _ptr(pool), staging_bytes, k_scale, v_scale)
         self._pool_keepalive = pool
         self.dtype = dtype
         h = ctypes.c_void_p()
@@ -252,7 +254,7 @@ class LKV:
         if st:
             raise LkvError(st, self.lib.lkv_last_error(None).decode())
         self.h = h
-        self.elem = 4 if dtype == "f32" else 2
+        self.elem = {"f32": 4, "bf16": 2, "fp8": 1}[dtype]   # bytes per element of the POOL
         self.token_bytes = 2 * num_kv_heads * head_dim * self.elem
         self.block_bytes = block_size * self.token_bytes
 

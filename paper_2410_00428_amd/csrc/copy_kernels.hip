@@ -70,6 +70,86 @@ write_kv_kernel(const char *__restrict__ K, const char *__restrict__ V, const in
     if (dst[u] >= 0) *(u32x4 *)(pool + dst[u]) = val[u];
 }
 
+
+// ---- 8-bit pool: bf16 in, E4M3 codes out.
+// Nearest E4M3 value of y (ties to the even code, +-448 past the largest value, NaN kept with its sign), in integer
+// arithmetic on the float's bits: the definition the kernel's fast path is checked against.
+__device__ __forceinline__ unsigned encode_e4m3(float y) {
+  const unsigned u = __float_as_uint(y), sign = (u >> 24) & 0x80u, a = u & 0x7FFFFFFFu;
+  if (a > 0x7F800000u) return sign | 0x7Fu;   // NaN
+  if (a >= 0x43E00000u) return sign | 0x7Eu;  // |y| >= 448, infinities included
+  if (a < 0x3C800000u)                        // |y| < 2^-6: multiples of 2^-9 (8 rounds up into the first normal)
+    return sign | (unsigned)__builtin_rintf(__uint_as_float(a) * 512.f);
+  const unsigned r = a + 0x0007FFFFu + ((a >> 20) & 1u);  // drop 20 mantissa bits, ties to even
+  return sign | ((r >> 20) - (120u << 3));                 // exponent re-biased 127 -> 7, 3 mantissa bits kept
+}
+
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+// One 16-byte piece of bf16 input (8 channels) per lane -> 8 bytes of codes.
+template <int UNROLL>
+__global__ void __launch_bounds__(kThreads)
+write_kv_e4m3_kernel(const char *__restrict__ K, const char *__restrict__ V, const int64_t *__restrict__ slots,
+                     char *__restrict__ pool, int64_t total_pieces, Div pieces_per_row, Div heads, Div block_size,
+                     int64_t in_row_bytes, int64_t row_bytes, int64_t block_bytes, float k_inv, float v_inv) {
+  int64_t base = ((int64_t)blockIdx.x * UNROLL) * kThreads + threadIdx.x;
+  u32x4 val[UNROLL];
+  int64_t dst[UNROLL];
+  float inv[UNROLL];
+#pragma unroll
+  for (int u = 0; u < UNROLL; ++u) {
+    int64_t i = base + (int64_t)u * kThreads;
+    dst[u] = -1;
+    if (i >= total_pieces) continue;
+    int64_t row, t2, t, blk;
+    uint32_t piece, h, kv, off;
+    divmod(i, pieces_per_row, row, piece);
+    divmod(row, heads, t2, h);
+    kv = (uint32_t)t2 & 1;
+    t = t2 >> 1;
+    int64_t slot = slots[t];
+    if (slot < 0) continue;
+    divmod(slot, block_size, blk, off);
+    const char *src = (kv ? V : K) + (t * heads.d + h) * in_row_bytes + (int64_t)piece * 16;
+    val[u] = __builtin_nontemporal_load((const u32x4 *)src);
+    inv[u] = kv ? v_inv : k_inv;
+    dst[u] = blk * block_bytes + ((int64_t)h * 2 + kv) * block_size.d * row_bytes + (int64_t)off * row_bytes +
+             (int64_t)piece * 8;
+  }
+#pragma unroll
+  for (int u = 0; u < UNROLL; ++u) {
+    if (dst[u] < 0) continue;
+    float y[8];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {  // a bf16 is the upper half of the float with the same value
+      y[2 * w] = __uint_as_float(val[u][w] << 16) * inv[u];
+      y[2 * w + 1] = __uint_as_float(val[u][w] & 0xFFFF0000u) * inv[u];
+    }
+    // The hardware conversion rounds to nearest even like encode_e4m3 (checked on every bf16 value); it is fed
+    // values clamped into the finite range (saturation), and a piece that holds a NaN takes the integer path, which
+    // keeps the NaN's sign.
+    u32x2 out;
+    const bool has_nan = __builtin_isunordered(y[0], y[1]) | __builtin_isunordered(y[2], y[3]) |
+                         __builtin_isunordered(y[4], y[5]) | __builtin_isunordered(y[6], y[7]);
+    if (!has_nan) {
+#pragma unroll
+      for (int w = 0; w < 8; ++w) y[w] = __builtin_amdgcn_fmed3f(y[w], -448.f, 448.f);
+      int lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], 0, false);
+      lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], lo, true);
+      int hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[4], y[5], 0, false);
+      hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[6], y[7], hi, true);
+      out = u32x2{(unsigned)lo, (unsigned)hi};
+    } else {
+      unsigned code[8];
+#pragma unroll
+      for (int w = 0; w < 8; ++w) code[w] = encode_e4m3(y[w]);
+      out = u32x2{code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24),
+                  code[4] | (code[5] << 8) | (code[6] << 16) | (code[7] << 24)};
+    }
+    *(u32x2 *)(pool + dst[u]) = out;
+  }
+}
+
 // GATHER: staging[i*beta + o] = pool[ids[i]*beta + o];  !GATHER: the inverse.
 template <bool GATHER, int UNROLL>
 __global__ void __launch_bounds__(kThreads)
@@ -115,6 +195,16 @@ namespace lkv {
 
 hipError_t launch_write_kv(const lkv_ctx *c, const void *K, const void *V, const int64_t *slots, int64_t num_tokens,
                            hipStream_t s) {
+  if (c->cfg.dtype == LKV_FP8_E4M3) {
+    const int64_t ppr = c->in_row_bytes / 16;
+    const int64_t total8 = num_tokens * 2 * c->cfg.num_kv_heads * ppr;
+    if (total8 == 0) return hipSuccess;
+    hipLaunchKernelGGL(write_kv_e4m3_kernel<kUnrollScatter>, dim3(grid_for(total8, kUnrollScatter)), dim3(kThreads), 0, s,
+                       (const char *)K, (const char *)V, slots, c->pool, total8, make_div(ppr),
+                       make_div(c->cfg.num_kv_heads), make_div(c->cfg.block_size), c->in_row_bytes, c->row_bytes,
+                       c->block_bytes, 1.0f / c->k_scale, 1.0f / c->v_scale);
+    return hipGetLastError();
+  }
   int64_t pieces_per_row = c->row_bytes / 16;
   int64_t total = num_tokens * 2 * c->cfg.num_kv_heads * pieces_per_row;
   if (total == 0) return hipSuccess;

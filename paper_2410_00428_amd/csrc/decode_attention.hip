@@ -391,14 +391,28 @@ __device__ __forceinline__ void decode_work_item(const int32_t *__restrict__ con
   }
 }
 
-template <int G, int WAVES>
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+// Eight E4M3 codes -> eight bf16 values (exact: every E4M3 value is a bf16 value); two codes per instruction.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32x4 widen_e4m3(u32x2 w) {
+  return u32x4{__builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w.x, 1.0f, false)),
+               __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w.x, 1.0f, true)),
+               __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w.y, 1.0f, false)),
+               __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w.y, 1.0f, true))};
+}
+
+template <int G, int WAVES, bool FP8>
 __global__ void __launch_bounds__(WAVES * 64)
 paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, const char *__restrict__ pool,
                          const int32_t *__restrict__ block_table, int max_blocks,
                          const int32_t *__restrict__ context_lens, int Hq, int64_t block_bytes, int pool_blocks,
-                         float scale, int partition, int num_parts, int num_seqs, int lpt_order, Workspace ws) {
+                         float scale, float out_scale, int partition, int num_parts, int num_seqs, int lpt_order,
+                         Workspace ws) {
+  // FP8: the pool holds one-byte E4M3 codes (rows of 128 bytes, pieces of 8 channels = 8 bytes); they are widened
+  // to bf16 in registers (exact) and take the same path; the K scale is part of `scale`, the V scale is out_scale.
   constexpr int D = 128;
-  constexpr int kRow = D * 2;  // bytes per key/value row
+  constexpr int kRow = FP8 ? D : D * 2;  // bytes per key/value row
+  constexpr int kPiece = FP8 ? 8 : 16;   // bytes of 8 channels
   const int Hkv = Hq / G;
   const int g = blockIdx.x % Hkv;  // kv head fastest: workgroups go round-robin to the XCDs
   int s = blockIdx.x / Hkv, part = 0;  // no context is split: one item per sequence
@@ -436,8 +450,8 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
   const int my_pairs = wave < npairs ? (npairs - wave + WAVES - 1) / WAVES : 0;
   const int32_t *table = block_table + (int64_t)s * max_blocks;
   // byte offsets inside a (block, head) run for the two roles of this lane
-  const int k_off = (8 * ((c >> 2) & 1) + (c & 3)) * kRow + 16 * hq;   // key row kappa_X(c) % 16, piece hq
-  const int v_off = kBlock * kRow + 8 * (hq & 1) * kRow + 16 * c;       // value rows 8*(hq%2)..+7, piece c
+  const int k_off = (8 * ((c >> 2) & 1) + (c & 3)) * kRow + kPiece * hq;   // key row kappa_X(c) % 16, piece hq
+  const int v_off = kBlock * kRow + 8 * (hq & 1) * kRow + kPiece * c;       // value rows 8*(hq%2)..+7, piece c
   const bool k_second = c >= 8, v_second = hq >= 2;                     // which block of the pair
   const int64_t head_off = (int64_t)g * (2 * kBlock * kRow);
 
@@ -457,6 +471,20 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
       const char *b1 = pool + (int64_t)id1 * block_bytes + head_off;
       const char *kb = (k_second ? b1 : b0) + k_off;
       const char *vb = (v_second ? b1 : b0) + v_off;
+      if (FP8) {  // raw codes travel in the first two words; compute() widens them once they have arrived
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          const u32x2 r = *(const u32x2 *)(kb + 32 * kk), t = *(const u32x2 *)(kb + 4 * kRow + 32 * kk);
+          kx[kk] = u32x4{r.x, r.y, 0u, 0u};
+          ky[kk] = u32x4{t.x, t.y, 0u, 0u};
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const u32x2 r = *(const u32x2 *)(vb + j * kRow);
+          vr[j] = u32x4{r.x, r.y, 0u, 0u};
+        }
+        return;
+      }
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) kx[kk] = *(const u32x4 *)(kb + 64 * kk);
 #pragma unroll
@@ -464,7 +492,17 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
 #pragma unroll
       for (int j = 0; j < 8; ++j) vr[j] = *(const u32x4 *)(vb + j * kRow);
     };
-    auto compute = [&](int it, const u32x4 *kx, const u32x4 *ky, u32x4 *vr) {
+    auto compute = [&](int it, const u32x4 *kx_in, const u32x4 *ky_in, u32x4 *vr) {
+      u32x4 kx[4], ky[4];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        kx[kk] = FP8 ? widen_e4m3(u32x2{kx_in[kk].x, kx_in[kk].y}) : kx_in[kk];
+        ky[kk] = FP8 ? widen_e4m3(u32x2{ky_in[kk].x, ky_in[kk].y}) : ky_in[kk];
+      }
+      if (FP8) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) vr[j] = widen_e4m3(u32x2{vr[j].x, vr[j].y});
+      }
       const int key0 = (nb_begin + 2 * (wave + (p0 + it) * WAVES)) * kBlock + 8 * hq;  // this lane's 8 keys
       f32x4 sx = {0.f, 0.f, 0.f, 0.f}, sy = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -555,7 +593,7 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
     }
     const int64_t row = (int64_t)s * Hq + g * G + j;
     if (num_parts == 1) {
-      Elem<uint16_t>::store(O + row * D + col, lt > 0.f ? ot / lt : 0.f);
+      Elem<uint16_t>::store(O + row * D + col, lt > 0.f ? ot / lt * out_scale : 0.f);
     } else {
       const int64_t p = row * num_parts + part;
       ws.o[p * D + col] = ot;
@@ -571,7 +609,7 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
 template <typename T, int D>
 __global__ void __launch_bounds__(D)
 decode_combine_kernel(T *__restrict__ O, const int32_t *__restrict__ context_lens, int Hq, int partition,
-                      int num_parts, Workspace ws) {
+                      int num_parts, float out_scale, Workspace ws) {
   const int64_t row = blockIdx.x;
   const int s = (int)(row / Hq), col = threadIdx.x;
   const int n = context_lens[s];
@@ -586,7 +624,7 @@ decode_combine_kernel(T *__restrict__ O, const int32_t *__restrict__ context_len
     lt += ws.ml[i * 2 + 1] * a;
     ot += ws.o[i * D + col] * a;
   }
-  Elem<T>::store(O + row * D + col, lt > 0.f ? ot / lt : 0.f);
+  Elem<T>::store(O + row * D + col, lt > 0.f ? ot / lt * out_scale : 0.f);
 }
 
 // Tunables of the split: tokens per partition and wavefronts per workgroup.  The host cannot see
@@ -604,7 +642,7 @@ Plan make_plan(const lkv_ctx *c, int num_seqs, int max_blocks) {
   const int64_t tokens = (int64_t)max_blocks * kBlock;
   const int64_t units = (int64_t)num_seqs * c->cfg.num_kv_heads;
   Plan p{0, 1, 4, false, false};
-  p.mfma = c->cfg.dtype == LKV_BF16 && c->cfg.head_dim == 128;
+  p.mfma = (c->cfg.dtype == LKV_BF16 || c->cfg.dtype == LKV_FP8_E4M3) && c->cfg.head_dim == 128;
   if (p.mfma) {
     // Measured on MI355X (sweep of partition 256..4096 x 2/4/8 wavefronts over batches of 1..256 sequences, contexts
     // of 200..16384 tokens, MHA and 8-fold GQA): partitions of 4096 tokens when the batch alone fills the chip
@@ -642,16 +680,17 @@ hipError_t launch_w(const lkv_ctx *c, const Plan &p, const void *Q, void *O, con
   return hipGetLastError();
 }
 
-template <int G, int WAVES>
+template <int G, int WAVES, bool FP8>
 hipError_t launch_mfma(const lkv_ctx *c, const Plan &p, const void *Q, void *O, const int32_t *bt, int max_blocks,
                        const int32_t *cl, int num_seqs, Workspace ws, hipStream_t s) {
   // one-dimensional grid, kv head fastest, then the rank of the (sequence, partition) work item
   if ((int64_t)c->cfg.num_kv_heads * num_seqs * p.num_parts > INT32_MAX) return hipErrorInvalidValue;
   dim3 grid((unsigned)(c->cfg.num_kv_heads * num_seqs * p.num_parts)), block(WAVES * 64);
   const int lpt = p.lpt ? 1 : 0;
-  hipLaunchKernelGGL((paged_decode_mfma_kernel<G, WAVES>), grid, block, 0, s, (const uint16_t *)Q,
+  hipLaunchKernelGGL((paged_decode_mfma_kernel<G, WAVES, FP8>), grid, block, 0, s, (const uint16_t *)Q,
                      (uint16_t *)O, c->pool, bt, max_blocks, cl, c->cfg.num_q_heads, c->block_bytes,
-                     (int)c->cfg.num_pool_blocks, c->scale, p.partition, p.num_parts, num_seqs, lpt, ws);
+                     (int)c->cfg.num_pool_blocks, FP8 ? c->scale * c->k_scale : c->scale, FP8 ? c->v_scale : 1.f,
+                     p.partition, p.num_parts, num_seqs, lpt, ws);
   return hipGetLastError();
 }
 
@@ -663,15 +702,22 @@ hipError_t launch_t(const lkv_ctx *c, const void *Q, void *O, const int32_t *bt,
   const int Hq = c->cfg.num_q_heads;
   Workspace ws{wsbuf, wsbuf + (int64_t)num_seqs * Hq * p.num_parts * 2};
   hipError_t e;
+  const bool fp8 = c->cfg.dtype == LKV_FP8_E4M3;
   if (p.mfma && sizeof(T) == 2 && D == 128) {  // make_plan sets mfma only for this case
-    e = p.waves == 2 ? launch_mfma<G, 2>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s)
-                     : launch_mfma<G, 8>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
+    if (fp8)
+      e = p.waves == 2 ? launch_mfma<G, 2, true>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s)
+                       : launch_mfma<G, 8, true>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
+    else
+      e = p.waves == 2 ? launch_mfma<G, 2, false>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s)
+                       : launch_mfma<G, 8, false>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
+  } else if (fp8) {
+    return hipErrorInvalidValue;  // 8-bit pools are only read by the kernel above (decode_supported says so)
   } else {
     e = launch_w<T, D, G, 4>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
   }
   if (e != hipSuccess || p.num_parts == 1) return e;
   hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(num_seqs * Hq), dim3(D), 0, s, (T *)O, cl, Hq, p.partition,
-                     p.num_parts, ws);
+                     p.num_parts, fp8 ? c->v_scale : 1.f, ws);
   return hipGetLastError();
 }
 
@@ -693,6 +739,7 @@ namespace lkv {
 
 bool decode_supported(const lkv_ctx *c) {
   const int g = c->cfg.num_q_heads / c->cfg.num_kv_heads;
+  if (c->cfg.dtype == LKV_FP8_E4M3 && c->cfg.head_dim != 128) return false;
   return c->cfg.block_size == kBlock && (c->cfg.head_dim == 64 || c->cfg.head_dim == 128) &&
          (g == 1 || g == 2 || g == 4 || g == 8);
 }

@@ -209,13 +209,16 @@ static lkv_status create_impl(const lkv_config *cfg, lkv_ctx **out, bool with_de
     return fail(nullptr, LKV_ERR_INVALID_ARG, "lkv_create: sizes must be positive");
   if (cfg->num_q_heads % cfg->num_kv_heads)
     return fail(nullptr, LKV_ERR_INVALID_ARG, "lkv_create: num_kv_heads must divide num_q_heads");
-  if (cfg->dtype != LKV_F32 && cfg->dtype != LKV_BF16)
+  if (cfg->dtype != LKV_F32 && cfg->dtype != LKV_BF16 && cfg->dtype != LKV_FP8_E4M3)
     return fail(nullptr, LKV_ERR_INVALID_ARG, "lkv_create: unknown dtype %d", cfg->dtype);
+  if (cfg->dtype == LKV_FP8_E4M3 && (!(cfg->k_scale >= 0.f) || !(cfg->v_scale >= 0.f) || std::isinf(cfg->k_scale) ||
+                                     std::isinf(cfg->v_scale)))
+    return fail(nullptr, LKV_ERR_INVALID_ARG, "lkv_create: k_scale and v_scale must be finite and positive (0 = 1.0)");
   if (cfg->num_pool_blocks > INT32_MAX)
     return fail(nullptr, LKV_ERR_INVALID_ARG, "lkv_create: block ids are 32-bit");
   if (cfg->decode_partition < 0 || cfg->decode_partition % 64)
     return fail(nullptr, LKV_ERR_INVALID_ARG, "lkv_create: decode_partition must be a multiple of 64");
-  int64_t elem = cfg->dtype == LKV_F32 ? 4 : 2;
+  int64_t elem = cfg->dtype == LKV_F32 ? 4 : cfg->dtype == LKV_BF16 ? 2 : 1;
   if ((cfg->head_dim * elem) % 16)
     return fail(nullptr, LKV_ERR_UNSUPPORTED, "lkv_create: head_dim*element size must be a multiple of 16 bytes");
   if (cfg->pool && ((uintptr_t)cfg->pool & 255))
@@ -226,6 +229,11 @@ static lkv_status create_impl(const lkv_config *cfg, lkv_ctx **out, bool with_de
   c->cfg = *cfg;
   c->elem = elem;
   c->row_bytes = cfg->head_dim * elem;
+  c->in_row_bytes = cfg->head_dim * (cfg->dtype == LKV_F32 ? 4 : 2);
+  if (cfg->dtype == LKV_FP8_E4M3) {
+    c->k_scale = cfg->k_scale > 0.f ? cfg->k_scale : 1.f;
+    c->v_scale = cfg->v_scale > 0.f ? cfg->v_scale : 1.f;
+  }
   c->token_bytes = 2 * cfg->num_kv_heads * c->row_bytes;
   c->block_bytes = cfg->block_size * c->token_bytes;
   c->scale = cfg->softmax_scale != 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);

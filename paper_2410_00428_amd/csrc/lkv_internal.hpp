@@ -55,6 +55,8 @@ struct lkv_ctx {
   int64_t token_bytes = 0;  // tau
   int64_t block_bytes = 0;  // beta
   float scale = 0.f;
+  float k_scale = 1.f, v_scale = 1.f;  // 8-bit pools: value = code * scale
+  int64_t in_row_bytes = 0;            // one head row of what lkv_write_kv is given (bf16 for 8-bit pools)
   char *pool = nullptr;
   bool owns_pool = false;
   bool logical_only = false;  // created without device resources: host state only

@@ -39,15 +39,15 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 
 
 def elem_size(dtype: str) -> int:
-    return {"f32": 4, "bf16": 2}[dtype]
+    return {"f32": 4, "bf16": 2, "fp8": 1}[dtype]   # "fp8": one-byte codes in the pool, bf16 everywhere else
 
 
 def storage_dtype(dtype: str):
-    return {"f32": np.float32, "bf16": np.uint16}[dtype]
+    return {"f32": np.float32, "bf16": np.uint16, "fp8": np.uint16}[dtype]   # of the tensors handed to the calls
 
 
 def to_f32(x: np.ndarray, dtype: str) -> np.ndarray:
-    return x.astype(np.float32) if dtype == "f32" else bf16_bits_to_f32(x)
+    return x.astype(np.float32) if dtype == "f32" else bf16_bits_to_f32(x)   # bf16 and fp8 pools: bf16 tensors
 
 
 # --------------------------------------------------------------------------- shapes / configs
@@ -58,7 +58,7 @@ class KVShape:
     num_kv_heads: int
     head_dim: int
     block_size: int
-    dtype: str  # "f32" | "bf16"
+    dtype: str  # "f32" | "bf16" | "fp8" (pool of E4M3 codes, tensors bf16)
 
     @property
     def token_bytes(self) -> int:  # tau: K and V of one token in one layer
@@ -158,7 +158,7 @@ def normal_tensor(rng: np.random.Generator, shape: Sequence[int], scale: float, 
     x = rng.standard_normal(tuple(shape), dtype=np.float32)
     if scale != 1.0:
         x *= np.float32(scale)
-    return x if dtype == "f32" else f32_to_bf16_bits(x)
+    return x if dtype == "f32" else f32_to_bf16_bits(x)   # also for "fp8": only the pool is 8-bit
 
 
 def qkv(config_number: int, layer: int, num_tokens: int, shape: KVShape, scale: float,

@@ -45,8 +45,9 @@ def make_pair(shape: wl.KVShape, num_blocks: int, free_order=None, **kw):
     pool = zero_pool(shape, num_blocks)
     c = lkv.LKV(shape.num_layers, shape.num_q_heads, shape.num_kv_heads, shape.head_dim, shape.block_size,
                 num_blocks, shape.dtype, pool=pool, **kw)
+    scales = {k: kw[k] for k in ("k_scale", "v_scale") if k in kw}
     o = orc.LayerKVOracle(shape.num_layers, shape.num_q_heads, shape.num_kv_heads, shape.head_dim,
-                          shape.block_size, num_blocks, shape.dtype)
+                          shape.block_size, num_blocks, shape.dtype, **scales)
     if free_order is not None:
         c.pool_reset(free_order)
         o.pool_reset(free_order)

@@ -99,3 +99,87 @@ def test_oracle_fp8_pool_decode_equals_decode_over_the_dequantised_values():
     rb = b.paged_decode_attention(q, bt, [n])
     assert np.allclose(ra, rb, rtol=1e-12, atol=1e-12)
     assert a.pack_layer_blocks(a.block_table(0, 0)).nbytes * 2 == b.pack_layer_blocks(b.block_table(0, 0)).nbytes
+
+
+# ----------------------------------------------------------------------------- library against the oracle (GPU)
+def _fp8_pair(Hq, Hkv, lens, k_scale, v_scale, seed, **kw):
+    from paper_2410_00428_amd import workloads as wl
+    from tests import gpu_harness as H
+    shape = wl.KVShape(1, Hq, Hkv, 128, 16, "fp8")
+    nblk = sum((n + 16) // 16 + 1 for n in lens) + 8
+    c, o, pool = H.make_pair(shape, nblk, wl.free_list_order(seed, nblk), k_scale=k_scale, v_scale=v_scale, **kw)
+    return shape, c, o, pool
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("Hq,Hkv,lens,part", [(8, 2, (300, 77, 515, 1, 64), 0), (4, 4, (130, 700), 64),
+                                              (16, 8, tuple([40] * 70), 0), (8, 1, (2500,), 0)])
+def test_fp8_pool_write_offload_reload_decode(Hq, Hkv, lens, part):
+    """8-bit pool end to end: the codes lkv_write_kv stores equal the oracle's bit for bit, an offload image is
+    those bytes (half the bf16 size), and decode attention over the codes matches the oracle within the bf16
+    tolerance - unsplit, split into 64-token partitions, with the library's own split of a small batch, and with
+    two-wavefront workgroups (70 x 8 kv heads)."""
+    from paper_2410_00428_amd import binding as lkv, workloads as wl
+    from tests import gpu_harness as H
+    k_scale, v_scale = 0.037, 0.0125
+    kw = dict(decode_partition=part) if part else {}
+    shape, c, o, pool = _fp8_pair(Hq, Hkv, lens, k_scale, v_scale, 41, **kw)
+    bf = wl.KVShape(1, Hq, Hkv, 128, 16, "bf16")
+    B, T = len(lens), sum(lens)
+    slots = []
+    for s, n in enumerate(lens):
+        c.alloc_layer_blocks(s, 0, n + 1)
+        o.alloc_layer_blocks(s, 0, n + 1)
+        slots.append(c.build_slot_mapping(s, 0, 0, n))
+        assert np.array_equal(slots[-1], o.slot_mapping(s, 0, 0, n))
+    slots = np.concatenate(slots)
+    _, K, V = wl.qkv(41, 0, T, bf, 1.0)
+    c.write_kv(0, H.to_dev(K), H.to_dev(V), H.to_dev(slots), T)
+    o.write_kv(K, V, slots)
+    torch.cuda.synchronize()
+    assert H.pool_as_oracle_view(pool, o).tobytes() == o.pool.tobytes(), "codes differ"
+    assert c.block_bytes == 16 * 2 * Hkv * 128
+    # offload image of sequence 0 and reload into the same blocks after wiping them
+    ids = c.get_block_table(0, 0)
+    buf = H.pinned_bytes(len(ids) * c.block_bytes)
+    c.pack_layer_blocks(0, ids, buf)
+    c.event_synchronize(0, lkv.LKV_EV_OFFLOADED)
+    assert buf.numpy()[:len(ids) * c.block_bytes].tobytes() == o.pack_layer_blocks(ids).tobytes()
+    pool.view(-1, c.block_bytes)[torch.from_numpy(ids.astype(np.int64)).to(H.DEV)] = 0x7F   # NaN codes everywhere
+    c.unpack_layer_blocks(0, ids, buf)
+    # one decode step: a new token per sequence, then attention over n + 1 positions
+    q, k1, v1 = wl.decode_qkv(41, 0, 0, B, bf, 1.0)
+    s1 = np.concatenate([c.build_slot_mapping(s, 0, n, 1) for s, n in enumerate(lens)])
+    c.write_kv(0, H.to_dev(k1), H.to_dev(v1), H.to_dev(s1), B)
+    o.write_kv(k1, v1, s1)
+    bt = c.padded_block_table(range(B), 0)
+    ctx = np.asarray([n + 1 for n in lens], dtype=np.int32)
+    Od = H.empty_like_storage(q.shape, "bf16")
+    Od.fill_(0x7FC0)
+    c.paged_decode_attention(0, H.to_dev(q), Od, H.to_dev(bt), bt.shape[1], H.to_dev(ctx), B)
+    ref = o.paged_decode_attention(q, bt, ctx, threads=8)
+    torch.cuda.synchronize()
+    assert H.pool_as_oracle_view(pool, o).tobytes() == o.pool.tobytes(), "codes differ after reload and append"
+    H.check_attention(H.to_host(Od, "bf16"), ref, "bf16", 1.0, "fp8 decode")
+    c.destroy()
+
+
+@pytest.mark.gpu
+def test_fp8_write_every_bf16_value_gets_the_oracles_code():
+    """All 65536 bf16 bit patterns (infinities, NaNs, zeros of both signs, denormals, values past 448 included)
+    through lkv_write_kv at three scales: the stored byte equals the oracle's code."""
+    from paper_2410_00428_amd import workloads as wl
+    from tests import gpu_harness as H
+    allbits = np.arange(65536, dtype=np.uint32).astype(np.uint16).reshape(256, 2, 128)   # 256 tokens, 2 heads
+    for k_scale, v_scale in ((1.0, 0.5), (0.037, 3.0), (1e-3, 448.0)):
+        shape, c, o, pool = _fp8_pair(2, 2, (256,), k_scale, v_scale, 42)
+        c.alloc_layer_blocks(0, 0, 256)
+        o.alloc_layer_blocks(0, 0, 256)
+        slots = c.build_slot_mapping(0, 0, 0, 256)
+        c.write_kv(0, H.to_dev(allbits), H.to_dev(allbits), H.to_dev(slots), 256)
+        o.write_kv(allbits, allbits, slots)
+        torch.cuda.synchronize()
+        got, want = H.pool_as_oracle_view(pool, o), o.pool
+        bad = np.argwhere(got != want)
+        assert len(bad) == 0, f"scales {k_scale}, {v_scale}: first differing element {bad[0]}: {got[tuple(bad[0])]:#x} vs {want[tuple(bad[0])]:#x}"
+        c.destroy()
