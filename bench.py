@@ -38,6 +38,8 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", type=int, default=2, choices=(2, 3))
+    ap.add_argument("--kv-dtype", default="bf16", choices=("bf16", "fp8"),
+                    help="fp8: the same step over an 8-bit pool (E4M3 codes); not the headline configuration")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget for the oracle timing")
     return ap.parse_args()
@@ -207,7 +209,14 @@ def main():
     L, B = sh.num_layers, len(w.prompt_lens)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    eng = LayerKVEngine(sh, w.pool_blocks, wl.free_list_order(w.number, w.pool_blocks))
+    eng_kw = {}
+    if args.kv_dtype == "fp8":
+        import dataclasses
+        w = dataclasses.replace(w, shape=dataclasses.replace(w.shape, dtype="fp8"), name=w.name + "-fp8pool")
+        sh = w.shape
+        eng_kw = dict(k_scale=w.data_scale / 16, v_scale=w.data_scale / 16)
+        args.no_cpu_baseline = True   # the timed oracle sample is the bf16 one
+    eng = LayerKVEngine(sh, w.pool_blocks, wl.free_list_order(w.number, w.pool_blocks), **eng_kw)
     T = sum(w.prompt_lens)
     gen = torch.Generator(device=dev)
     gen.manual_seed(wl.SEED_BASE + w.number)
@@ -488,7 +497,7 @@ def main():
     iso["prefill_attn_TFLOPs"] = pf_flops / (t_prefill * 1e-3) / 1e12
     iso["decode_paged_attn_GBps"] = decode_bytes_per_launch[0] / (t_decode * 1e-3) / 1e9
     iso = {k: (round(v, 2) if isinstance(v, float) else v) for k, v in iso.items()}
-    traffic = TRAFFIC_BYTES.get(args.workload)
+    traffic = TRAFFIC_BYTES.get(args.workload) if args.kv_dtype == "bf16" else None
     # what a pure bf16 MFMA stream sustains on this machine right now (random operand bits, as in real data; then
     # constant operands): the published peak assumes the boost clock, which a matrix load does not hold
     torch.cuda.synchronize()

@@ -471,7 +471,7 @@ lkv_status lkv_write_kv(lkv_ctx *c, int32_t layer, const void *K, const void *V,
     hipEvent_t t0;
     if (lkv_status st = timed_begin(c, s, &t0)) return st;
     LKV_HIP(c, lkv::launch_write_kv(c, K, V, slot_mapping, num_tokens, s));
-    if (lkv_status st = timed_end(c, s, t0, 2 * num_tokens * c->token_bytes, lkv_ctx::kTimedWrite)) return st;
+    if (lkv_status st = timed_end(c, s, t0, num_tokens * (2 * c->cfg.num_kv_heads * c->in_row_bytes + c->token_bytes), lkv_ctx::kTimedWrite)) return st;
   }
   c->stats.write_kv_calls += 1;
   c->stats.write_kv_bytes += num_tokens * c->token_bytes;
