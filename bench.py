@@ -41,6 +41,8 @@ def parse_args():
     ap.add_argument("--kv-dtype", default="bf16", choices=("bf16", "fp8"),
                     help="fp8: the same step over an 8-bit pool (E4M3 codes); not the headline configuration")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the figures of the other workloads' decode batches and of the 8-bit pool (profiling runs)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget for the oracle timing")
     return ap.parse_args()
 
@@ -503,8 +505,8 @@ def main():
     torch.cuda.synchronize()
     mf_rand = c.probe_mfma_rate(30.0, True, eng.main)
     mf_const = c.probe_mfma_rate(30.0, False, eng.main)
-    others = decode_other_workloads(torch, dev)
-    fp8_fig = fp8_pool_figures(torch, dev)
+    others = None if args.no_extras else decode_other_workloads(torch, dev)
+    fp8_fig = None if args.no_extras else fp8_pool_figures(torch, dev)
 
     out = {
         "metric": METRIC, "value": round(decode_gbs, 2), "unit": "GB/s",
