@@ -35,7 +35,9 @@
  *             lkv_last_error() gives a text for the last failure on that context.  Arguments
  *             the host can see (layer range, NULL pointers, counts, ids given as host arrays)
  *             are validated; indices that live in device memory (slot_mapping, block_table,
- *             context_lens) are the caller's responsibility: they must lie inside the pool.
+ *             context_lens) are the caller's responsibility: they must lie inside the pool (the
+ *             kernels skip a slot and clamp a table entry outside it rather than touch memory
+ *             outside the pool; the results are then wrong, not a fault).
  *   Threads   a context is not thread-safe; use one thread per context or lock outside.
  *
  * Storage format of the pool (also the format of an offloaded image)
@@ -238,7 +240,9 @@ lkv_status lkv_pressure_offload(int64_t deficit_blocks, const int32_t *retained,
 
 /* ------------------------------------------------------------------ device hot path */
 /* K, V: device, [num_tokens][num_kv_heads][head_dim], contiguous.  slot_mapping: device,
- * int64[num_tokens]; token t goes to slot slot_mapping[t]; a negative slot skips the token.
+ * int64[num_tokens]; token t goes to slot slot_mapping[t]; a negative slot skips the token, and so does a slot
+ * past the end of the pool (a caller's mistake that must not write outside it).  With an LKV_FP8_E4M3 pool K and V
+ * are bf16 and are stored as codes (see lkv_dtype).
  * Waits (on `stream`) for LKV_EV_RELOADED of the layer, then records LKV_EV_KV_WRITTEN of
  * `layer` on `stream`.  (Sections 2.1.1, 3.2.1) */
 lkv_status lkv_write_kv(lkv_ctx *ctx, int32_t layer, const void *K, const void *V,

@@ -42,7 +42,7 @@ template <int UNROLL>
 __global__ void __launch_bounds__(kThreads)
 write_kv_kernel(const char *__restrict__ K, const char *__restrict__ V, const int64_t *__restrict__ slots,
                 char *__restrict__ pool, int64_t total_pieces, Div pieces_per_row, Div heads, Div block_size,
-                int64_t row_bytes, int64_t block_bytes) {
+                int64_t row_bytes, int64_t block_bytes, int64_t pool_slots) {
   int64_t base = ((int64_t)blockIdx.x * UNROLL) * kThreads + threadIdx.x;
   u32x4 val[UNROLL];
   int64_t dst[UNROLL];
@@ -58,7 +58,7 @@ write_kv_kernel(const char *__restrict__ K, const char *__restrict__ V, const in
     kv = (uint32_t)t2 & 1;
     t = t2 >> 1;
     int64_t slot = slots[t];
-    if (slot < 0) continue;
+    if (slot < 0 || slot >= pool_slots) continue;  // negative = skip; past the pool = a caller's mistake, not written
     divmod(slot, block_size, blk, off);
     const char *src = (kv ? V : K) + (t * heads.d + h) * row_bytes + (int64_t)piece * 16;
     val[u] = __builtin_nontemporal_load((const u32x4 *)src);
@@ -91,7 +91,8 @@ template <int UNROLL>
 __global__ void __launch_bounds__(kThreads)
 write_kv_e4m3_kernel(const char *__restrict__ K, const char *__restrict__ V, const int64_t *__restrict__ slots,
                      char *__restrict__ pool, int64_t total_pieces, Div pieces_per_row, Div heads, Div block_size,
-                     int64_t in_row_bytes, int64_t row_bytes, int64_t block_bytes, float k_inv, float v_inv) {
+                     int64_t in_row_bytes, int64_t row_bytes, int64_t block_bytes, int64_t pool_slots, float k_inv,
+                     float v_inv) {
   int64_t base = ((int64_t)blockIdx.x * UNROLL) * kThreads + threadIdx.x;
   u32x4 val[UNROLL];
   int64_t dst[UNROLL];
@@ -108,7 +109,7 @@ write_kv_e4m3_kernel(const char *__restrict__ K, const char *__restrict__ V, con
     kv = (uint32_t)t2 & 1;
     t = t2 >> 1;
     int64_t slot = slots[t];
-    if (slot < 0) continue;
+    if (slot < 0 || slot >= pool_slots) continue;  // negative = skip; past the pool = a caller's mistake, not written
     divmod(slot, block_size, blk, off);
     const char *src = (kv ? V : K) + (t * heads.d + h) * in_row_bytes + (int64_t)piece * 16;
     val[u] = __builtin_nontemporal_load((const u32x4 *)src);
@@ -202,7 +203,7 @@ hipError_t launch_write_kv(const lkv_ctx *c, const void *K, const void *V, const
     hipLaunchKernelGGL(write_kv_e4m3_kernel<kUnrollScatter>, dim3(grid_for(total8, kUnrollScatter)), dim3(kThreads), 0, s,
                        (const char *)K, (const char *)V, slots, c->pool, total8, make_div(ppr),
                        make_div(c->cfg.num_kv_heads), make_div(c->cfg.block_size), c->in_row_bytes, c->row_bytes,
-                       c->block_bytes, 1.0f / c->k_scale, 1.0f / c->v_scale);
+                       c->block_bytes, c->cfg.num_pool_blocks * c->cfg.block_size, 1.0f / c->k_scale, 1.0f / c->v_scale);
     return hipGetLastError();
   }
   int64_t pieces_per_row = c->row_bytes / 16;
@@ -210,7 +211,8 @@ hipError_t launch_write_kv(const lkv_ctx *c, const void *K, const void *V, const
   if (total == 0) return hipSuccess;
   hipLaunchKernelGGL(write_kv_kernel<kUnrollScatter>, dim3(grid_for(total, kUnrollScatter)), dim3(kThreads), 0, s, (const char *)K, (const char *)V,
                      slots, c->pool, total, make_div(pieces_per_row), make_div(c->cfg.num_kv_heads),
-                     make_div(c->cfg.block_size), c->row_bytes, c->block_bytes);
+                     make_div(c->cfg.block_size), c->row_bytes, c->block_bytes,
+                     c->cfg.num_pool_blocks * c->cfg.block_size);
   return hipGetLastError();
 }
 

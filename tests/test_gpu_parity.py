@@ -326,6 +326,28 @@ def test_write_kv_negative_slots_and_empty_calls():
     c.destroy()
 
 
+def test_write_kv_skips_slots_outside_the_pool():
+    """A slot past the end of the pool is a caller's mistake: the token is dropped, nothing outside the pool is
+    written (a guard tensor allocated right behind the pool keeps its pattern) and the other tokens land."""
+    shape = wl.KVShape(1, 2, 2, 128, 16, "bf16")
+    nblk = 4
+    guard = 1 << 20
+    buf = torch.zeros(nblk * shape.block_bytes + guard, dtype=torch.uint8, device=H.DEV)
+    buf[nblk * shape.block_bytes:] = 0xA5
+    c = lkv.LKV(1, 2, 2, 128, 16, nblk, "bf16", pool=buf)
+    o = orc.LayerKVOracle(1, 2, 2, 128, 16, nblk, "bf16")
+    _, K, V = wl.qkv(20, 0, 8, shape, 1.0)
+    slots = np.array([0, nblk * 16, 5, nblk * 16 + 7, 63, 2 ** 40, -1, 17], dtype=np.int64)
+    c.write_kv(0, H.to_dev(K), H.to_dev(V), H.to_dev(slots), 8)
+    keep = np.where((slots >= 0) & (slots < nblk * 16), slots, -1)
+    o.write_kv(K, V, keep)
+    torch.cuda.synchronize()
+    got = buf.cpu().numpy()
+    assert got[:nblk * shape.block_bytes].view(np.uint16).reshape(o.pool.shape).tobytes() == o.pool.tobytes()
+    assert (got[nblk * shape.block_bytes:] == 0xA5).all()
+    c.destroy()
+
+
 def test_pack_unpack_in_many_chunks_and_on_a_side_stream():
     """Staging smaller than the image: chunked transfers, more chunks than id-ring slots, side stream."""
     shape = wl.KVShape(2, 4, 4, 64, 16, "bf16")   # block = 16 KiB
