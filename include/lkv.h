@@ -318,7 +318,7 @@ lkv_status lkv_set_link_gate(lkv_ctx *ctx, lkv_link_busy_fn busy, void *user, in
  * device, [num_seqs][num_q_heads][head_dim]; block_table: device, int32[num_seqs][max_blocks_per_seq]
  * (entries past ceil(context_len/bs) are ignored; every entry before that must be a block id of the pool: the
  * kernels clamp an entry outside [0, num_pool_blocks) into the pool, which gives a wrong row but touches no memory
- * outside the pool); context_lens: device, int32[num_seqs];
+ * outside the pool); context_lens: device, int32[num_seqs] (a value above 16*max_blocks_per_seq is cut there);
  * sequence s attends to positions 0..context_lens[s]-1; a zero context gives a zero row.
  * Waits (on `stream`) for LKV_EV_RELOADED of the layer.  Long contexts are split into
  * partitions whose partial results are merged by a second kernel; the split-K workspace is

@@ -17,6 +17,10 @@
 namespace {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// A context never reaches past its row of the block table: a longer one (a caller's mistake) is cut there, so that
+// no table entry outside the row is read and no partition outside the grid is expected.
+__device__ __forceinline__ int capped(int n, int cap) { return n < cap ? n : cap; }
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 constexpr int kBlock = 16;  // tokens per KV block these kernels are built for
@@ -84,7 +88,7 @@ paged_decode_kernel(const T *__restrict__ Q, T *__restrict__ O, const char *__re
   constexpr bool kPrefetch = G <= 2;        // two blocks in flight per wavefront while registers allow
 
   const int g = blockIdx.x, s = blockIdx.y, part = blockIdx.z;  // partition index slowest: see make_plan
-  const int n = context_lens[s];
+  const int n = capped(context_lens[s], max_blocks * kBlock);
   const int start = part * partition;
   if (start >= n && part != 0) return;
   const int end = min(n, start + partition);
@@ -286,11 +290,11 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
 // whole partition each while the rest of the chip is idle.  Ranks past the list have nothing to do.
 // Every lane returns the same (seq, part); seq < 0 = nothing to do.  Built for num_seqs <= 256.
 __device__ __forceinline__ void decode_work_item(const int32_t *__restrict__ context_lens, int num_seqs, int partition,
-                                                 int rank, int &seq, int &part) {
+                                                 int cap, int rank, int &seq, int &part) {
   const int lane = threadIdx.x & 63;
   if (num_seqs <= 64) {
     // the whole batch fits one register per lane: one load, scalar walks over the lanes (v_readlane)
-    const int n = lane < num_seqs ? context_lens[lane] : -1;
+    const int n = lane < num_seqs ? capped(context_lens[lane], cap) : -1;
     const int f = n > 0 ? n / partition : 0;                                          // full partitions
     const int r = n == 0 ? 0 : (n > 0 && n % partition != 0) ? n % partition : -1;   // remainder, -1 = none
     int acc = 0;
@@ -322,7 +326,7 @@ __device__ __forceinline__ void decode_work_item(const int32_t *__restrict__ con
   // full partitions, sequence order
   for (int b0 = 0; b0 < num_seqs; b0 += 64) {
     const int s = b0 + lane;
-    const int n = s < num_seqs ? context_lens[s] : 0;
+    const int n = s < num_seqs ? capped(context_lens[s], cap) : 0;
     const int f = n > 0 ? n / partition : 0;
     int incl = f;
 #pragma unroll
@@ -350,7 +354,7 @@ __device__ __forceinline__ void decode_work_item(const int32_t *__restrict__ con
   int num_cand = 0;
   for (int b0 = 0; b0 < num_seqs; b0 += 64) {
     const int s = b0 + lane;
-    const int n = s < num_seqs ? context_lens[s] : -1;
+    const int n = s < num_seqs ? capped(context_lens[s], cap) : -1;
     num_cand += __popcll(__ballot(n == 0 || (n > 0 && n % partition != 0)));
   }
   if (r_rank >= num_cand) {  // past the end of the work list
@@ -360,13 +364,13 @@ __device__ __forceinline__ void decode_work_item(const int32_t *__restrict__ con
   }
   for (int b0 = 0; b0 < num_seqs; b0 += 64) {
     const int s = b0 + lane;
-    const int n = s < num_seqs ? context_lens[s] : -1;
+    const int n = s < num_seqs ? capped(context_lens[s], cap) : -1;
     const bool cand = n == 0 || (n > 0 && n % partition != 0);
     const int r = n > 0 ? n % partition : 0;
     int my_rank = 0;
     for (int t0 = 0; t0 < num_seqs; t0 += 64) {
       const int t = t0 + lane;
-      const int nt = t < num_seqs ? context_lens[t] : -1;
+      const int nt = t < num_seqs ? capped(context_lens[t], cap) : -1;
       // remainder of sequence t, or -1 if it has no partial partition (never counted: r >= 0)
       const int rt = nt == 0 ? 0 : (nt > 0 && nt % partition != 0) ? nt % partition : -1;
       const int kmax = min(64, num_seqs - t0);
@@ -418,16 +422,16 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
   int s = blockIdx.x / Hkv, part = 0;  // no context is split: one item per sequence
   if (num_parts > 1) {
     if (lpt_order) {
-      decode_work_item(context_lens, num_seqs, partition, blockIdx.x / Hkv, s, part);
+      decode_work_item(context_lens, num_seqs, partition, max_blocks * kBlock, blockIdx.x / Hkv, s, part);
     } else {
       const int rank = blockIdx.x / Hkv;
       s = rank % num_seqs;
       part = rank / num_seqs;
-      if (part * partition >= context_lens[s] && part != 0) s = -1;
+      if (part * partition >= capped(context_lens[s], max_blocks * kBlock) && part != 0) s = -1;
     }
   }
   if (s < 0) return;
-  const int n = context_lens[s];
+  const int n = capped(context_lens[s], max_blocks * kBlock);
   const int start = part * partition;
   const int end = min(n, start + partition);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -608,11 +612,11 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
 // One workgroup per (sequence, q head): merges the partitions that the context spans.
 template <typename T, int D>
 __global__ void __launch_bounds__(D)
-decode_combine_kernel(T *__restrict__ O, const int32_t *__restrict__ context_lens, int Hq, int partition,
+decode_combine_kernel(T *__restrict__ O, const int32_t *__restrict__ context_lens, int cap, int Hq, int partition,
                       int num_parts, float out_scale, Workspace ws) {
   const int64_t row = blockIdx.x;
   const int s = (int)(row / Hq), col = threadIdx.x;
-  const int n = context_lens[s];
+  const int n = capped(context_lens[s], cap);
   const int parts = n <= 0 ? 0 : (n + partition - 1) / partition;
   float mn = -INFINITY;
   for (int p = 0; p < parts; ++p) mn = fmaxf(mn, ws.ml[(row * num_parts + p) * 2]);
@@ -716,7 +720,8 @@ hipError_t launch_t(const lkv_ctx *c, const void *Q, void *O, const int32_t *bt,
     e = launch_w<T, D, G, 4>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
   }
   if (e != hipSuccess || p.num_parts == 1) return e;
-  hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(num_seqs * Hq), dim3(D), 0, s, (T *)O, cl, Hq, p.partition,
+  hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(num_seqs * Hq), dim3(D), 0, s, (T *)O, cl, max_blocks * kBlock, Hq,
+                     p.partition,
                      p.num_parts, fp8 ? c->v_scale : 1.f, ws);
   return hipGetLastError();
 }

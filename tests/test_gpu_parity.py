@@ -271,6 +271,30 @@ def test_decode_small_batches_get_smaller_partitions_from_the_plan(Hq, Hkv, lens
     sc.close()
 
 
+@pytest.mark.parametrize("partition", [0, 64])
+def test_decode_cuts_a_context_that_reaches_past_its_table_row(partition):
+    """A context length larger than the table row holds is a caller's mistake; the kernels attend over the row's
+    blocks only (no table entry outside the row is read) and give what the oracle gives for the cut length."""
+    shape = wl.KVShape(1, 4, 2, 128, 16, "bf16")
+    lens = (160, 47, 96)           # the first sequence fills the table row (10 blocks) exactly
+    kw = dict(decode_partition=partition) if partition else {}
+    sc = Scenario(21, shape, lens, 32, **kw)
+    sc.prefill_layer(0, check_attn=False)
+    q, _, _ = wl.decode_qkv(21, 0, 0, 3, shape, 1.0)
+    bt = sc.c.padded_block_table(range(3), 0)
+    assert bt.shape[1] == 10
+    ctx = np.asarray([160 + 5000, 47, 2 ** 30], dtype=np.int32)
+    cut = np.minimum(ctx, np.asarray([160, 47, 96]))   # sequence 2: its row holds 6 blocks, the rest is -1 padding
+    Od = H.empty_like_storage(q.shape, "bf16")
+    sc.c.paged_decode_attention(0, H.to_dev(q), Od, H.to_dev(bt), bt.shape[1], H.to_dev(ctx), 3)
+    torch.cuda.synchronize()
+    got = H.to_host(Od, "bf16")
+    ref = sc.o.paged_decode_attention(q, bt, cut, threads=ORC_THREADS)
+    H.check_attention(got[:2], ref[:2], "bf16", 1.0, "contexts cut at the table row")
+    assert np.isfinite(got[2]).all()    # its padding entries are clamped into the pool: wrong keys, but no fault
+    sc.close()
+
+
 def test_decode_zero_context_and_poisoned_unused_slots():
     """context 0 gives a zero row; NaN in unused slots (tail of the last block, stale blocks) must not leak."""
     shape = wl.KVShape(1, 4, 2, 128, 16, "bf16")
