@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--kv-dtype", default="bf16", choices=("bf16", "fp8"),
                     help="fp8: the same step over an 8-bit pool (E4M3 codes); not the headline configuration")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-offload", action="store_true",
+                    help="keep every layer on the GPU: a step without host-link traffic (profiling runs: under "
+                         "rocprofv3 copies run as shader kernels and slow the kernels next to them)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the figures of the other workloads' decode batches and of the 8-bit pool (profiling runs)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget for the oracle timing")
@@ -237,7 +240,7 @@ def main():
     dk = [randn(B, sh.num_kv_heads, sh.head_dim) for _ in range(L)]
     dv = [randn(B, sh.num_kv_heads, sh.head_dim) for _ in range(L)]
     dO = torch.empty_like(dq[0])
-    off_layers = list(w.offload_layers)
+    off_layers = [] if args.no_offload else list(w.offload_layers)
     layer_bytes = sum(wl.blocks_for(n, sh.block_size) for n in w.prompt_lens) * sh.block_bytes
     pinned = {l: eng.pinned(layer_bytes) for l in off_layers}
 
@@ -381,7 +384,6 @@ def main():
         iso["offload_GBps"] = layer_bytes * len(off_layers) / (t_link * 1e-3) / 1e9
         iso["reload_GBps"] = layer_bytes * len(off_layers) / (t_reload * 1e-3) / 1e9
         # the same layers through the pageable tier: ordinary host memory behind the library's small pinned ring
-        import numpy as np
         pageable = np.ones(layer_bytes * len(off_layers), dtype=np.uint8)   # touched before timing
         views = {l: pageable[i * layer_bytes:(i + 1) * layer_bytes] for i, l in enumerate(off_layers)}
         t_page = {}
