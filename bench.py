@@ -37,7 +37,14 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", type=int, default=2, choices=(2, 3))
+    ap.add_argument("--workload", type=int, default=2, choices=(2, 3, 5),
+                    help="2 (default, the headline configuration), 3, or 5: the mixed serving iteration with the "
+                         "decode batch's host layers in ordinary host memory (needs ~200 GiB of host memory at 64 "
+                         "decode sequences)")
+    ap.add_argument("--decode-seqs", type=int, default=64, help="workload 5: decoding sequences (64 = the full size)")
+    ap.add_argument("--ring-layers", type=int, default=3, help="workload 5: sets of blocks the host layers pass through")
+    ap.add_argument("--tier-threads", type=int, default=8,
+                    help="workload 5: CPU threads that copy between the pinned ring and ordinary host memory")
     ap.add_argument("--kv-dtype", default="bf16", choices=("bf16", "fp8"),
                     help="fp8: the same step over an 8-bit pool (E4M3 codes); not the headline configuration")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -54,13 +61,14 @@ def causal_flops(lens, Hq, d):
     return 4.0 * d * Hq * sum(n * (n + 1) / 2 for n in lens)
 
 
-def cpu_baseline(w, seconds: float) -> dict:
+def cpu_baseline(w, seconds: float, lens=None) -> dict:
     """The oracle as it stands, timed on the host: paged decode attention of ONE layer of the
-    workload (all sequences, all heads, fp64 accumulators), repeated until ~`seconds` are spent."""
+    workload (all sequences unless `lens` names a sample of them, all heads, fp64 accumulators), repeated until
+    ~`seconds` are spent."""
     from oracle import layerkv_oracle as orc
     from paper_2410_00428_amd import workloads as wl
     sh = w.shape
-    lens = [n + 1 for n in w.prompt_lens]
+    lens = list(lens) if lens is not None else [n + 1 for n in w.prompt_lens]
     nblk = sum(wl.blocks_for(n, sh.block_size) for n in lens)
     o = orc.LayerKVOracle(1, sh.num_q_heads, sh.num_kv_heads, sh.head_dim, sh.block_size, nblk, sh.dtype)
     o.pool_reset(wl.free_list_order(w.number, nblk, index=77))
@@ -95,7 +103,7 @@ def cpu_baseline(w, seconds: float) -> dict:
     flops_rows = float(sum(4.0 * sh.head_dim * (r + 1) for r in tok))
     return {"value": round(kv_bytes * reps / el / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
             "sample": f"paged decode attention of one layer of workload {w.number} ({len(lens)} seqs x "
-                      f"{sh.num_q_heads} heads, context {lens[0]}, {kv_bytes / 2**20:.0f} MiB KV), fp64 accumulators, "
+                      f"{sh.num_q_heads} heads, contexts {min(lens)}..{max(lens)}, {kv_bytes / 2**20:.0f} MiB KV), fp64 accumulators, "
                       f"{reps} repetitions in {el:.1f} s",
             "prefill_tflops": round(flops_rows / t_rows / 1e12, 6),
             "prefill_sample": f"{len(tok)} sampled causal rows of one {n0}-token prompt"}
@@ -200,11 +208,164 @@ def fp8_pool_figures(torch, dev) -> dict:
     return out
 
 
+def mixed_iteration(args) -> None:
+    """Workload 5 at its full size: 64 decoding sequences (contexts uniform in [128, 16384], ~8 GiB of KV per
+    layer) of which 24 of 32 layers live in ORDINARY host memory (~194 GiB) and come back through a ring of
+    blocks, plus two new 8192-token prompts that prefill and offload in the same iteration.  One step = one such
+    iteration over all layers.  The iteration is bound by the host link by construction (the paper's extreme
+    case); `value` is still the decode kernel's rate, by the library's events inside the iteration."""
+    import torch
+    from paper_2410_00428_amd import workloads as wl
+    from paper_2410_00428_amd.serving import MixedIteration
+
+    def say(msg):
+        print(f"[bench workload 5] {msg}", file=sys.stderr, flush=True)
+
+    w = wl.workload(5, decode_seqs_cfg5=args.decode_seqs)
+    sh = w.shape
+    L, bs = sh.num_layers, sh.block_size
+    dlens, plens, host = list(w.decode_lens), list(w.prompt_lens), list(w.offload_layers)
+    B, Td, T = len(dlens), sum(dlens), sum(plens)
+    dblk = sum(wl.blocks_for(n, bs) for n in dlens)
+    pblk = sum(wl.blocks_for(n, bs) for n in plens)
+    R = args.ring_layers
+    nblk = (L - len(host) + R) * dblk + L * pblk + 64
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    say(f"{B} decode sequences, {Td} cached tokens per layer = {dblk * sh.block_bytes / 2**30:.2f} GiB per layer; "
+        f"pool {nblk} blocks = {nblk * sh.block_bytes / 2**30:.1f} GiB; host images "
+        f"{len(host) * dblk * sh.block_bytes / 2**30:.1f} GiB")
+    it = MixedIteration(sh, dlens, plens, host, nblk, ring_layers=R, free_order=wl.free_list_order(5, nblk),
+                        tier_units=8, tier_threads=args.tier_threads)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(wl.SEED_BASE + 5)
+
+    def randn(n, h):   # in pieces: the fp32 draw of a 4 GiB tensor would need 8 GiB more
+        out = torch.empty(n, h, sh.head_dim, dtype=torch.bfloat16, device=dev)
+        for a in range(0, n, 1 << 16):
+            b = min(n, a + (1 << 16))
+            out[a:b] = torch.randn(b - a, h, sh.head_dim, generator=gen, device=dev) * w.data_scale
+        return out
+
+    Kd, Vd = randn(Td, sh.num_kv_heads), randn(Td, sh.num_kv_heads)
+    # queries scaled so that the softmax is neither uniform nor one-hot at these context lengths
+    q_dec = [randn(B, sh.num_q_heads) * 0.25 for _ in range(L)]
+    O_ref = torch.zeros(L, B, sh.num_q_heads, sh.head_dim, dtype=torch.bfloat16, device=dev)
+    O_dec = torch.zeros_like(O_ref)
+    n_in = 4
+    pq = [(randn(T, sh.num_q_heads) * 0.25, randn(T, sh.num_kv_heads), randn(T, sh.num_kv_heads)) for _ in range(n_in)]
+    O_pf = torch.empty_like(pq[0][0])
+    t0 = time.perf_counter()
+    # layers alternate between the two tensors' roles so that neighbouring layers hold different bytes
+    it.build_cached_state(lambda l: (Kd, Vd) if l % 2 == 0 else (Vd, Kd),
+                          while_resident=lambda l: it.decode_layer(l, q_dec[l], O_ref[l]),
+                          progress=lambda m: say(f"{m} ({time.perf_counter() - t0:.1f} s)"))
+    torch.cuda.synchronize()
+    t_build = time.perf_counter() - t0
+    del Kd, Vd
+
+    def iteration():
+        it.run(q_dec, O_dec, lambda l: pq[l % n_in], O_pf)
+        it.finish()
+        it.drop_prompts()
+
+    for i in range(args.warmup):
+        t1 = time.perf_counter()
+        iteration()
+        say(f"warm-up iteration {i}: {time.perf_counter() - t1:.3f} s")
+    exact = bool(torch.equal(O_dec, O_ref)) if args.warmup else None
+    it.ctx.set_profiling(True)
+    s0 = it.ctx.get_stats()
+    walls = []
+    for i in range(args.steps):
+        O_dec.zero_()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        iteration()
+        walls.append(time.perf_counter() - t1)
+        say(f"iteration {i}: {walls[-1]:.3f} s")
+        exact = bool(torch.equal(O_dec, O_ref)) and exact is not False
+    st = it.ctx.get_stats()
+    it.ctx.set_profiling(False)
+    K = args.steps
+    d = {k: st[k] - s0[k] for k in st if isinstance(st[k], int)}
+    wall = sum(walls) / K
+    kv_bytes = Td * sh.token_bytes
+    decode_gbs = kv_bytes * L * K / max(d["decode_kernel_ns"], 1)
+    assert d["decode_kernel_launches"] == L * K and d["prefill_kernel_launches"] == L * K
+    pf_flops = causal_flops(plens, sh.num_q_heads, sh.head_dim)
+    prefill_tflops = pf_flops * L * K / max(d["prefill_kernel_ns"], 1) / 1e3
+    reload_bytes = len(host) * dblk * sh.block_bytes
+    offload_bytes = len(host) * pblk * sh.block_bytes
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+    link = {}
+    big = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    big_host = torch.empty(1 << 30, dtype=torch.uint8, pin_memory=True)
+    for name, dst, src in (("d2h", big_host, big), ("h2d", big, big_host)):
+        dst.copy_(src, non_blocking=True)
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(2):
+            dst.copy_(src, non_blocking=True)
+        b.record()
+        torch.cuda.synchronize()
+        link[name] = 2 * (1 << 30) / (a.elapsed_time(b) * 1e-3) / 1e9
+    del big, big_host
+    reload_gbs = reload_bytes / wall / 1e9
+    out = {
+        "metric": METRIC, "value": round(decode_gbs, 2), "unit": "GB/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": round(wall * 1e3, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"5: {w.name} (L={L}, Hq={sh.num_q_heads}, Hkv={sh.num_kv_heads}, d={sh.head_dim}, block 16, "
+                               f"{B} decoding sequences with contexts {min(dlens)}..{max(dlens)} ({Td} tokens), "
+                               f"{len(host)} of {L} layers of them in ordinary host memory and reloaded through a ring of "
+                               f"{R} sets of blocks, {len(plens)} new prompts x {plens[0]} tokens prefilled and offloaded "
+                               f"in the same iteration)",
+                   "value_is": "decode paged attention: context KV bytes / HIP-event time of the decode launches "
+                               "(library events), measured inside the iteration"},
+        "components": {
+            "decode_paged_attn_GBps": round(decode_gbs, 2),
+            "decode_frac_of_hbm_peak": round(decode_gbs / HBM_PEAK_GBS, 4),
+            "decode_ms_per_layer": round(d["decode_kernel_ns"] * 1e-6 / (L * K), 4),
+            "prefill_attn_TFLOPs": round(prefill_tflops, 2),
+            "prefill_frac_of_bf16_mfma_peak": round(prefill_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+            "prefill_ms_per_layer": round(d["prefill_kernel_ns"] * 1e-6 / (L * K), 4),
+            "write_kv_GBps": round(d["write_kernel_bytes"] / max(d["write_kernel_ns"], 1), 2),
+            "pack_kernel_GBps": round(d["pack_kernel_bytes"] / max(d["pack_kernel_ns"], 1), 2),
+            "unpack_kernel_GBps": round(d["unpack_kernel_bytes"] / max(d["unpack_kernel_ns"], 1), 2),
+            "reload_GiB_per_iteration": round(reload_bytes / 2**30, 2),
+            "offload_GiB_per_iteration": round(offload_bytes / 2**30, 2),
+            "reload_GBps_over_the_iteration": round(reload_gbs, 2),
+            "pinned_copy_peak_GBps": {k: round(v, 2) for k, v in link.items()},
+            "reload_frac_of_link_peak": round(reload_gbs / link["h2d"], 4),
+            "gpu_kernel_ms_per_iteration": round((d["decode_kernel_ns"] + d["prefill_kernel_ns"] + d["write_kernel_ns"]
+                                                  + d["pack_kernel_ns"] + d["unpack_kernel_ns"]) * 1e-6 / K, 2),
+            "iteration_s": [round(x, 3) for x in walls],
+        },
+        "memory": {"pool_GiB": round(nblk * sh.block_bytes / 2**30, 1),
+                   "host_images_GiB": round((reload_bytes + offload_bytes) / 2**30, 1),
+                   "pinned_MiB": 8 * 32, "tier_threads": args.tier_threads, "build_cached_state_s": round(t_build, 1)},
+        "decode_after_reload_equals_decode_before_offload": exact,
+        "roofline": {"kernel": "paged_decode_mfma_kernel (lkv_paged_decode_attention)", "bound": "hbm",
+                     "achieved": round(decode_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(decode_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "launch_ms": round(d["decode_kernel_ns"] * 1e-6 / (L * K), 4), "bytes_per_launch": kv_bytes},
+    }
+    it.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds, lens=sorted(dlens)[len(dlens) // 2 - 1:len(dlens) // 2 + 1])
+    print(json.dumps(out))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.workload == 5:
+        return mixed_iteration(args)
     import torch
     from paper_2410_00428_amd import workloads as wl
     from paper_2410_00428_amd.engine import LayerKVEngine

@@ -169,7 +169,61 @@ lkv_status check_ids(const lkv_ctx *c, const int32_t *ids, int64_t n) {
   return LKV_OK;
 }
 
-// Kernel profiling: brackets one launch with timing events taken from a small free list.
+// Adds one finished (start, stop) pair to the statistics and hands its events back to the free list.
+void fold_one(lkv_ctx *c, const lkv_ctx::Timed &t, float ms) {
+  const int64_t ns = (int64_t)((double)ms * 1e6);
+  switch (t.kind) {
+    case lkv_ctx::kTimedUnpack:
+      c->stats.unpack_kernel_ns += ns;
+      c->stats.unpack_kernel_bytes += t.bytes;
+      break;
+    case lkv_ctx::kTimedPack:
+      c->stats.pack_kernel_ns += ns;
+      c->stats.pack_kernel_bytes += t.bytes;
+      break;
+    case lkv_ctx::kTimedWrite:
+      c->stats.write_kernel_ns += ns;
+      c->stats.write_kernel_launches += 1;
+      c->stats.write_kernel_bytes += t.bytes;
+      break;
+    case lkv_ctx::kTimedPrefill:
+      c->stats.prefill_kernel_ns += ns;
+      c->stats.prefill_kernel_launches += 1;
+      break;
+    default:
+      c->stats.decode_kernel_ns += ns;
+      c->stats.decode_kernel_launches += 1;
+      break;
+  }
+  c->spare_events.push_back(t.a);
+  c->spare_events.push_back(t.b);
+}
+
+// Folds the profiled launches into the statistics: all of them (wait = true: blocks until each has finished), or
+// only those that have finished already (wait = false), the others staying in the list.
+lkv_status fold_timed(lkv_ctx *c, bool wait) {
+  size_t kept = 0;
+  for (size_t i = 0; i < c->timed.size(); ++i) {
+    const lkv_ctx::Timed t = c->timed[i];
+    if (wait) {
+      LKV_HIP(c, hipEventSynchronize(t.b));
+    } else if (hipEventQuery(t.b) != hipSuccess) {
+      (void)hipGetLastError();  // "not ready" is an answer, not an error: do not leave it for the next launch check
+      c->timed[kept++] = t;
+      continue;
+    }
+    float ms = 0.f;
+    LKV_HIP(c, hipEventElapsedTime(&ms, t.a, t.b));
+    fold_one(c, t, ms);
+  }
+  c->timed.resize(kept);
+  return LKV_OK;
+}
+
+// Kernel profiling: brackets one launch with timing events taken from a small free list.  A transfer of many
+// units profiles thousands of launches between two reads of the statistics: finished pairs are folded on the
+// way, whenever kTimedBacklog more have been added, so that the number of live events stays bounded.
+constexpr size_t kTimedBacklog = 512;
 lkv_status timed_begin(lkv_ctx *c, hipStream_t s, hipEvent_t *a) {
   *a = nullptr;
   if (!c->profiling) return LKV_OK;
@@ -194,6 +248,10 @@ lkv_status timed_end(lkv_ctx *c, hipStream_t s, hipEvent_t a, int64_t bytes, int
   }
   LKV_HIP(c, hipEventRecord(b, s));
   c->timed.push_back({a, b, bytes, kind});
+  if (c->timed.size() >= c->timed_fold_at) {
+    if (lkv_status st = fold_timed(c, false)) return st;
+    c->timed_fold_at = c->timed.size() + kTimedBacklog;
+  }
   return LKV_OK;
 }
 
@@ -771,38 +829,8 @@ lkv_status lkv_probe_mfma_rate(lkv_ctx *c, double millis, int32_t random_operand
 
 lkv_status lkv_get_stats(lkv_ctx *c, lkv_stats *out, int64_t size) {
   if (!c || !out || size < 0) return LKV_ERR_INVALID_ARG;
-  for (auto &t : c->timed) {
-    LKV_HIP(c, hipEventSynchronize(t.b));
-    float ms = 0.f;
-    LKV_HIP(c, hipEventElapsedTime(&ms, t.a, t.b));
-    const int64_t ns = (int64_t)((double)ms * 1e6);
-    switch (t.kind) {
-      case lkv_ctx::kTimedUnpack:
-        c->stats.unpack_kernel_ns += ns;
-        c->stats.unpack_kernel_bytes += t.bytes;
-        break;
-      case lkv_ctx::kTimedPack:
-        c->stats.pack_kernel_ns += ns;
-        c->stats.pack_kernel_bytes += t.bytes;
-        break;
-      case lkv_ctx::kTimedWrite:
-        c->stats.write_kernel_ns += ns;
-        c->stats.write_kernel_launches += 1;
-        c->stats.write_kernel_bytes += t.bytes;
-        break;
-      case lkv_ctx::kTimedPrefill:
-        c->stats.prefill_kernel_ns += ns;
-        c->stats.prefill_kernel_launches += 1;
-        break;
-      default:
-        c->stats.decode_kernel_ns += ns;
-        c->stats.decode_kernel_launches += 1;
-        break;
-    }
-    c->spare_events.push_back(t.a);
-    c->spare_events.push_back(t.b);
-  }
-  c->timed.clear();
+  if (lkv_status st = fold_timed(c, true)) return st;
+  c->timed_fold_at = kTimedBacklog;
   c->stats.tier_copy_bytes = c->tier.copied_bytes();
   c->stats.tier_copy_ns = c->tier.copy_ns();
   c->stats.ring_wait_ns = c->tier.ring_wait_ns();

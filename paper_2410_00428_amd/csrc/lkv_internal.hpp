@@ -90,6 +90,7 @@ struct lkv_ctx {
   int32_t gate_max_checks = 0;
   bool profiling = false;
   std::vector<Timed> timed;
+  size_t timed_fold_at = 512;  // list length at which finished pairs are folded on the way
   std::vector<hipEvent_t> spare_events;
   mutable std::string err;
 };
