@@ -8,7 +8,9 @@ layers pack + copy to pinned host memory on a side stream; then reload those lay
 decode step (append one token per sequence per layer, paged decode attention).  Inputs are
 resident in HBM before the timed region starts.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2|3] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2|3|5] [--no-cpu-baseline]
+
+--workload 5 is a different step: one mixed serving iteration at full size (see mixed_iteration below).
 """
 from __future__ import annotations
 
