@@ -94,7 +94,9 @@ typedef enum {
 typedef struct {
   int32_t num_layers;
   int32_t num_q_heads;
-  int32_t num_kv_heads;     /* must divide num_q_heads; q head h uses kv head h/(Hq/Hkv)      */
+  int32_t num_kv_heads;     /* must divide num_q_heads; q head h uses kv head h/(Hq/Hkv).  Decode
+                             * attention: Hq/Hkv <= 16 for bf16 / 8-bit pools with head_dim 128, <= 8
+                             * otherwise (LKV_ERR_UNSUPPORTED beyond); prefill takes any ratio           */
   int32_t head_dim;         /* attention kernels: 64 or 128; head_dim*e must be a multiple of 16 */
   int32_t block_size;       /* tokens per block; attention kernels: 16                         */
   int32_t dtype;            /* lkv_dtype                                                       */

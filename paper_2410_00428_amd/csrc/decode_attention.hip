@@ -79,7 +79,10 @@ template <typename T, int D, int G, int WAVES>
 __global__ void __launch_bounds__(WAVES * 64)
 paged_decode_kernel(const T *__restrict__ Q, T *__restrict__ O, const char *__restrict__ pool,
                     const int32_t *__restrict__ block_table, int max_blocks, const int32_t *__restrict__ context_lens,
-                    int Hq, int64_t block_bytes, int pool_blocks, float scale, int partition, int num_parts, Workspace ws) {
+                    int Hq, int group, int64_t block_bytes, int pool_blocks, float scale, int partition, int num_parts,
+                    Workspace ws) {
+  // G is the register capacity: the kernel serves `group` <= G query heads per kv head (the heads past `group`
+  // repeat the last one and are dropped at the end), so that 3, 5, 6 and 7 heads per kv head run as 4 resp. 8.
   constexpr int EPL = Elem<T>::kPerPiece;   // elements per 16-byte piece
   constexpr int LPR = D / EPL;              // lanes per row
   constexpr int TPI = 64 / LPR;             // tokens covered by one wavefront load
@@ -98,7 +101,7 @@ paged_decode_kernel(const T *__restrict__ Q, T *__restrict__ O, const char *__re
   float q[G][EPL];
 #pragma unroll
   for (int j = 0; j < G; ++j) {
-    u32x4 w = *(const u32x4 *)(Q + ((int64_t)s * Hq + g * G + j) * D + c * EPL);
+    u32x4 w = *(const u32x4 *)(Q + ((int64_t)s * Hq + g * group + min(j, group - 1)) * D + c * EPL);
     Elem<T>::unpack(w, q[j]);
 #pragma unroll
     for (int e = 0; e < EPL; ++e) q[j][e] *= scale;
@@ -230,7 +233,7 @@ paged_decode_kernel(const T *__restrict__ Q, T *__restrict__ O, const char *__re
     }
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < G * D; idx += WAVES * 64) {
+  for (int idx = threadIdx.x; idx < group * D; idx += WAVES * 64) {
     const int j = idx / D, col = idx % D;
     float mn = -INFINITY;
 #pragma unroll
@@ -243,7 +246,7 @@ paged_decode_kernel(const T *__restrict__ Q, T *__restrict__ O, const char *__re
       lt += sm_ml[w][j][1] * a;
       ot += sm_o[w][j][col] * a;
     }
-    const int64_t row = (int64_t)s * Hq + g * G + j;
+    const int64_t row = (int64_t)s * Hq + g * group + j;
     if (num_parts == 1) {
       Elem<T>::store(O + row * D + col, lt > 0.f ? ot / lt : 0.f);
     } else {
@@ -409,15 +412,17 @@ template <int G, int WAVES, bool FP8>
 __global__ void __launch_bounds__(WAVES * 64)
 paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, const char *__restrict__ pool,
                          const int32_t *__restrict__ block_table, int max_blocks,
-                         const int32_t *__restrict__ context_lens, int Hq, int64_t block_bytes, int pool_blocks,
-                         float scale, float out_scale, int partition, int num_parts, int num_seqs, int lpt_order,
-                         Workspace ws) {
+                         const int32_t *__restrict__ context_lens, int Hq, int group, int64_t block_bytes,
+                         int pool_blocks, float scale, float out_scale, int partition, int num_parts, int num_seqs,
+                         int lpt_order, Workspace ws) {
+  // G is the capacity (LDS rows of the merge) for `group` <= G query heads per kv head: the heads are columns of
+  // the matrix products, of which there are 16 whatever the group size.
   // FP8: the pool holds one-byte E4M3 codes (rows of 128 bytes, pieces of 8 channels = 8 bytes); they are widened
   // to bf16 in registers (exact) and take the same path; the K scale is part of `scale`, the V scale is out_scale.
   constexpr int D = 128;
   constexpr int kRow = FP8 ? D : D * 2;  // bytes per key/value row
   constexpr int kPiece = FP8 ? 8 : 16;   // bytes of 8 channels
-  const int Hkv = Hq / G;
+  const int Hkv = Hq / group;
   const int g = blockIdx.x % Hkv;  // kv head fastest: workgroups go round-robin to the XCDs
   int s = blockIdx.x / Hkv, part = 0;  // no context is split: one item per sequence
   if (num_parts > 1) {
@@ -441,7 +446,7 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
     u32x4 w = {0, 0, 0, 0};
-    if (c < G) w = *(const u32x4 *)(Q + ((int64_t)s * Hq + g * G + c) * D + 32 * kk + 8 * hq);
+    if (c < group) w = *(const u32x4 *)(Q + ((int64_t)s * Hq + g * group + c) * D + 32 * kk + 8 * hq);
     qop[kk] = __builtin_bit_cast(bf16x8, w);
   }
   f32x4 oacc[8];
@@ -571,7 +576,7 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
   // merge the wavefronts through LDS; lane (q, hq) owns channels 32*hq + 8*v + i of query q
   __shared__ float sm_ml[WAVES][G][2];
   __shared__ float sm_o[WAVES][G][D];
-  if (c < G) {
+  if (c < group) {
     if (hq == 0) {
       sm_ml[wave][c][0] = m;
       sm_ml[wave][c][1] = l;
@@ -582,7 +587,7 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
       for (int v = 0; v < 4; ++v) sm_o[wave][c][32 * hq + 8 * v + i] = oacc[i][v];
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < G * D; idx += WAVES * 64) {
+  for (int idx = threadIdx.x; idx < group * D; idx += WAVES * 64) {
     const int j = idx / D, col = idx % D;
     float mn = -INFINITY;
 #pragma unroll
@@ -595,7 +600,7 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
       lt += sm_ml[w][j][1] * a;
       ot += sm_o[w][j][col] * a;
     }
-    const int64_t row = (int64_t)s * Hq + g * G + j;
+    const int64_t row = (int64_t)s * Hq + g * group + j;
     if (num_parts == 1) {
       Elem<uint16_t>::store(O + row * D + col, lt > 0.f ? ot / lt * out_scale : 0.f);
     } else {
@@ -680,7 +685,7 @@ hipError_t launch_w(const lkv_ctx *c, const Plan &p, const void *Q, void *O, con
                     const int32_t *cl, int num_seqs, Workspace ws, hipStream_t s) {
   hipLaunchKernelGGL((paged_decode_kernel<T, D, G, WAVES>), dim3(c->cfg.num_kv_heads, num_seqs, p.num_parts),
                      dim3(WAVES * 64), 0, s, (const T *)Q, (T *)O, c->pool, bt, max_blocks, cl, c->cfg.num_q_heads,
-                     c->block_bytes, (int)c->cfg.num_pool_blocks, c->scale, p.partition, p.num_parts, ws);
+                     c->cfg.num_q_heads / c->cfg.num_kv_heads, c->block_bytes, (int)c->cfg.num_pool_blocks, c->scale, p.partition, p.num_parts, ws);
   return hipGetLastError();
 }
 
@@ -692,8 +697,8 @@ hipError_t launch_mfma(const lkv_ctx *c, const Plan &p, const void *Q, void *O, 
   dim3 grid((unsigned)(c->cfg.num_kv_heads * num_seqs * p.num_parts)), block(WAVES * 64);
   const int lpt = p.lpt ? 1 : 0;
   hipLaunchKernelGGL((paged_decode_mfma_kernel<G, WAVES, FP8>), grid, block, 0, s, (const uint16_t *)Q,
-                     (uint16_t *)O, c->pool, bt, max_blocks, cl, c->cfg.num_q_heads, c->block_bytes,
-                     (int)c->cfg.num_pool_blocks, FP8 ? c->scale * c->k_scale : c->scale, FP8 ? c->v_scale : 1.f,
+                     (uint16_t *)O, c->pool, bt, max_blocks, cl, c->cfg.num_q_heads,
+                     c->cfg.num_q_heads / c->cfg.num_kv_heads, c->block_bytes, (int)c->cfg.num_pool_blocks, FP8 ? c->scale * c->k_scale : c->scale, FP8 ? c->v_scale : 1.f,
                      p.partition, p.num_parts, num_seqs, lpt, ws);
   return hipGetLastError();
 }
@@ -716,8 +721,10 @@ hipError_t launch_t(const lkv_ctx *c, const void *Q, void *O, const int32_t *bt,
                        : launch_mfma<G, 8, false>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
   } else if (fp8) {
     return hipErrorInvalidValue;  // 8-bit pools are only read by the kernel above (decode_supported says so)
-  } else {
+  } else if constexpr (G <= 8) {
     e = launch_w<T, D, G, 4>(c, p, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
+  } else {
+    return hipErrorInvalidValue;  // more than 8 heads per kv head only on the matrix-core kernel
   }
   if (e != hipSuccess || p.num_parts == 1) return e;
   hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(num_seqs * Hq), dim3(D), 0, s, (T *)O, cl, max_blocks * kBlock, Hq,
@@ -729,12 +736,12 @@ hipError_t launch_t(const lkv_ctx *c, const void *Q, void *O, const int32_t *bt,
 template <typename T, int D>
 hipError_t launch_g(const lkv_ctx *c, const void *Q, void *O, const int32_t *bt, int max_blocks, const int32_t *cl,
                     int num_seqs, float *ws, hipStream_t s) {
-  switch (c->cfg.num_q_heads / c->cfg.num_kv_heads) {
-    case 1: return launch_t<T, D, 1>(c, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
-    case 2: return launch_t<T, D, 2>(c, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
-    case 4: return launch_t<T, D, 4>(c, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
-    case 8: return launch_t<T, D, 8>(c, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
-  }
+  const int group = c->cfg.num_q_heads / c->cfg.num_kv_heads;   // the smallest built capacity that holds it
+  if (group == 1) return launch_t<T, D, 1>(c, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
+  if (group == 2) return launch_t<T, D, 2>(c, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
+  if (group <= 4) return launch_t<T, D, 4>(c, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
+  if (group <= 8) return launch_t<T, D, 8>(c, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
+  if (group <= 16) return launch_t<T, D, 16>(c, Q, O, bt, max_blocks, cl, num_seqs, ws, s);
   return hipErrorInvalidValue;
 }
 
@@ -745,8 +752,10 @@ namespace lkv {
 bool decode_supported(const lkv_ctx *c) {
   const int g = c->cfg.num_q_heads / c->cfg.num_kv_heads;
   if (c->cfg.dtype == LKV_FP8_E4M3 && c->cfg.head_dim != 128) return false;
-  return c->cfg.block_size == kBlock && (c->cfg.head_dim == 64 || c->cfg.head_dim == 128) &&
-         (g == 1 || g == 2 || g == 4 || g == 8);
+  // query heads per kv head: up to 16 on the matrix-core kernel (bf16 or 8-bit pool, head_dim 128), up to 8 otherwise
+  const bool mfma = c->cfg.dtype != LKV_F32 && c->cfg.head_dim == 128;
+  return c->cfg.block_size == kBlock && (c->cfg.head_dim == 64 || c->cfg.head_dim == 128) && g >= 1 &&
+         g <= (mfma ? 16 : 8);
 }
 
 int64_t decode_workspace_bytes(const lkv_ctx *c, int32_t num_seqs, int32_t max_blocks) {

@@ -766,8 +766,9 @@ lkv_status lkv_paged_decode_attention(lkv_ctx *c, int32_t layer, const void *Q, 
   if (bad_layer(c, layer) || num_seqs < 0 || max_blocks_per_seq < 0)
     return fail(c, LKV_ERR_INVALID_ARG, "lkv_paged_decode_attention: bad layer or count");
   if (!lkv::decode_supported(c))
-    return fail(c, LKV_ERR_UNSUPPORTED, "lkv_paged_decode_attention: head_dim %d / block_size %d / dtype %d is not built",
-                c->cfg.head_dim, c->cfg.block_size, c->cfg.dtype);
+    return fail(c, LKV_ERR_UNSUPPORTED,
+                "lkv_paged_decode_attention: head_dim %d / block_size %d / dtype %d / %d query heads per kv head is not built",
+                c->cfg.head_dim, c->cfg.block_size, c->cfg.dtype, c->cfg.num_q_heads / c->cfg.num_kv_heads);
   if (num_seqs == 0) return LKV_OK;
   if (!Q || !O || !context_lens || (max_blocks_per_seq && !block_table))
     return fail(c, LKV_ERR_INVALID_ARG, "lkv_paged_decode_attention: NULL pointer");

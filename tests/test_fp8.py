@@ -114,7 +114,8 @@ def _fp8_pair(Hq, Hkv, lens, k_scale, v_scale, seed, **kw):
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("Hq,Hkv,lens,part", [(8, 2, (300, 77, 515, 1, 64), 0), (4, 4, (130, 700), 64),
-                                              (16, 8, tuple([40] * 70), 0), (8, 1, (2500,), 0)])
+                                              (16, 8, tuple([40] * 70), 0), (8, 1, (2500,), 0),
+                                              (14, 2, (300, 77, 33), 0)])
 def test_fp8_pool_write_offload_reload_decode(Hq, Hkv, lens, part):
     """8-bit pool end to end: the codes lkv_write_kv stores equal the oracle's bit for bit, an offload image is
     those bytes (half the bf16 size), and decode attention over the codes matches the oracle within the bf16

@@ -219,6 +219,41 @@ def test_f32_head_dim_128_and_gqa():
     sc.close()
 
 
+@pytest.mark.parametrize("Hq,Hkv,d,dtype,partition", [
+    (14, 2, 128, "bf16", 0),     # 7 query heads per kv head (the 34B model of the paper's evaluation: 56 over 8)
+    (56, 8, 128, "bf16", 64),    # that model's head counts, split decode
+    (12, 4, 128, "bf16", 0),     # 3
+    (16, 1, 128, "bf16", 0),     # 16: every column of the matrix product in use
+    (11, 1, 128, "bf16", 128),   # 11, in the capacity-16 kernel
+    (6, 2, 64, "bf16", 0),       # 3 on the vector kernel (head_dim 64)
+    (10, 2, 64, "bf16", 64),     # 5
+    (6, 2, 128, "f32", 0),       # 3, fp32
+    (7, 1, 64, "f32", 64)])      # 7, fp32
+def test_group_sizes_that_are_not_powers_of_two(Hq, Hkv, d, dtype, partition):
+    """Decode kernels are built for 1, 2, 4, 8 and 16 query heads per kv head and serve the sizes in between with
+    the next capacity; prefill takes any ratio.  Section 5.1 evaluates a model with 7 query heads per kv head."""
+    shape = wl.KVShape(1, Hq, Hkv, d, 16, dtype)
+    lens = (150, 37, 260) if Hq < 56 else (150, 37)
+    sc = Scenario(16, shape, lens, 64, decode_partition=partition)
+    sc.prefill_layer(0)
+    sc.decode_step(0)
+    sc.decode_step(0, step=1, append=False)
+    sc.close()
+
+
+def test_decode_refuses_more_query_heads_per_kv_head_than_the_kernels_hold():
+    for Hq, d, dtype in ((17, 128, "bf16"), (9, 64, "bf16"), (9, 128, "f32")):
+        shape = wl.KVShape(1, Hq, 1, d, 16, dtype)
+        c, o, pool = H.make_pair(shape, 8)
+        c.alloc_layer_blocks(0, 0, 16)
+        q = H.empty_like_storage((1, Hq, d), dtype)
+        with pytest.raises(lkv.LkvError) as e:
+            c.paged_decode_attention(0, q, torch.empty_like(q), H.to_dev(c.padded_block_table([0], 0)), 1,
+                                     H.to_dev(np.asarray([16], np.int32)), 1)
+        assert e.value.status == lkv.LKV_ERR_UNSUPPORTED
+        c.destroy()
+
+
 # ----------------------------------------------------------------------------- split-K decode
 @pytest.mark.parametrize("partition", [0, 64, 128, 1024])
 def test_decode_split_k_is_independent_of_partition_size(partition):
