@@ -210,6 +210,25 @@ def fp8_pool_figures(torch, dev) -> dict:
     return out
 
 
+def pinned_copy_peak(torch, dev) -> dict:
+    """What one large hipMemcpyAsync between pinned host memory and the device reaches, per direction (GB/s)."""
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+    link = {}
+    big = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    big_host = torch.empty(1 << 30, dtype=torch.uint8, pin_memory=True)
+    for name, dst, src in (("d2h", big_host, big), ("h2d", big, big_host)):
+        dst.copy_(src, non_blocking=True)
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(2):
+            dst.copy_(src, non_blocking=True)
+        b.record()
+        torch.cuda.synchronize()
+        link[name] = 2 * (1 << 30) / (a.elapsed_time(b) * 1e-3) / 1e9
+    return link
+
+
 def mixed_iteration(args) -> None:
     """Workload 5 at its full size: 64 decoding sequences (contexts uniform in [128, 16384], ~8 GiB of KV per
     layer) of which 24 of 32 layers live in ORDINARY host memory (~194 GiB) and come back through a ring of
@@ -300,21 +319,7 @@ def mixed_iteration(args) -> None:
     reload_bytes = len(host) * dblk * sh.block_bytes
     offload_bytes = len(host) * pblk * sh.block_bytes
 
-    def ev():
-        return torch.cuda.Event(enable_timing=True)
-    link = {}
-    big = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-    big_host = torch.empty(1 << 30, dtype=torch.uint8, pin_memory=True)
-    for name, dst, src in (("d2h", big_host, big), ("h2d", big, big_host)):
-        dst.copy_(src, non_blocking=True)
-        a, b = ev(), ev()
-        a.record()
-        for _ in range(2):
-            dst.copy_(src, non_blocking=True)
-        b.record()
-        torch.cuda.synchronize()
-        link[name] = 2 * (1 << 30) / (a.elapsed_time(b) * 1e-3) / 1e9
-    del big, big_host
+    link = pinned_copy_peak(torch, dev)
     reload_gbs = reload_bytes / wall / 1e9
     out = {
         "metric": METRIC, "value": round(decode_gbs, 2), "unit": "GB/s",
@@ -488,19 +493,7 @@ def main():
     # ---- outside the timed steps: the host link's own peak, and how much of the offload hides behind prefill
     def ev():
         return torch.cuda.Event(enable_timing=True)
-    link = {}
-    big = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-    big_host = eng.pinned(1 << 30)
-    for name, dst, src in (("d2h", big_host, big), ("h2d", big, big_host)):
-        dst.copy_(src, non_blocking=True)
-        a, b = ev(), ev()
-        a.record()
-        for _ in range(2):
-            dst.copy_(src, non_blocking=True)
-        b.record()
-        torch.cuda.synchronize()
-        link[name] = 2 * (1 << 30) / (a.elapsed_time(b) * 1e-3) / 1e9
-    del big, big_host
+    link = pinned_copy_peak(torch, dev)
 
     def prefill_phase(offload):
         """offload: False, True (the workload's layers) or an explicit {layer: pinned buffer}."""

@@ -11,8 +11,7 @@ paper's equations.  Only ``tests/`` may import it.
 * Section 3.2.1, Eq. 5: free-block forecast; the pressure rule (x/2 layers of the most recent
   requests first, then the rest).
 
-Readings of what the paper leaves open are listed in the design doc (G21-G27); every function states the
-one it takes.
+Where the paper leaves something open, the function concerned states the reading it takes.
 """
 from __future__ import annotations
 

@@ -1,4 +1,4 @@
-"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times (through
+"""GPU parity at the benchmark configurations' full sizes, in the launch configuration bench.py times (through
 ``LayerKVEngine``), on outputs the oracle can compute one by one: sampled causal rows, whole decode
 steps, byte-exact pools and offload images.  Workloads 2-5; where a workload is cut down for the
 CPU side's sake the deviation is stated in the test."""
