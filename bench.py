@@ -91,6 +91,29 @@ def cpu_baseline(w, seconds: float, lens=None) -> dict:
         el = time.perf_counter() - t0
         if el > seconds:
             break
+    t1 = time.perf_counter()
+    o.paged_decode_attention(q, bt, lens, threads=1)
+    decode_1core = kv_bytes / (time.perf_counter() - t1) / 1e9
+    # the byte movers of the same layer: write of every token's K/V, gather of the layer's blocks, scatter back
+    ids = sum((o.block_table(s, 0) for s in range(len(lens))), [])
+    slots = np.concatenate([o.slot_mapping(s, 0, 0, n) for s, n in enumerate(lens)])
+    Kw, Vw = (wl.normal_tensor(rng, (sum(lens), sh.num_kv_heads, sh.head_dim), w.data_scale, sh.dtype) for _ in range(2))
+    t1 = time.perf_counter()
+    o.write_kv(Kw, Vw, slots)
+    t_write = time.perf_counter() - t1
+    t1 = time.perf_counter()
+    image = o.pack_layer_blocks(ids)
+    t_pack = time.perf_counter() - t1
+    t1 = time.perf_counter()
+    o.unpack_layer_blocks(ids, image)
+    t_unpack = time.perf_counter() - t1
+    movers = {"decode_GBps_1_core": round(decode_1core, 3),
+              "write_kv_GBps": round(2 * kv_bytes / t_write / 1e9, 3),
+              "pack_GBps": round(2 * len(ids) * sh.block_bytes / t_pack / 1e9, 3),
+              "unpack_GBps": round(2 * len(ids) * sh.block_bytes / t_unpack / 1e9, 3),
+              "movers_note": "oracle write / pack / unpack of the same layer, bytes read + written, one call each, "
+                             "single-threaded numpy"}
+    del Kw, Vw, image
     # a second figure for the contraction: causal prefill on a seeded sample of query rows
     T = sum(w.prompt_lens)
     n0 = w.prompt_lens[0]
@@ -108,7 +131,7 @@ def cpu_baseline(w, seconds: float, lens=None) -> dict:
                       f"{sh.num_q_heads} heads, contexts {min(lens)}..{max(lens)}, {kv_bytes / 2**20:.0f} MiB KV), fp64 accumulators, "
                       f"{reps} repetitions in {el:.1f} s",
             "prefill_tflops": round(flops_rows / t_rows / 1e12, 6),
-            "prefill_sample": f"{len(tok)} sampled causal rows of one {n0}-token prompt"}
+            "prefill_sample": f"{len(tok)} sampled causal rows of one {n0}-token prompt", **movers}
 
 
 def decode_other_workloads(torch, dev) -> dict:
