@@ -266,6 +266,12 @@ def mixed_iteration(args) -> None:
         print(f"[bench workload 5] {msg}", file=sys.stderr, flush=True)
 
     w = wl.workload(5, decode_seqs_cfg5=args.decode_seqs)
+    kw = {}
+    if args.kv_dtype == "fp8":   # the same iteration over an 8-bit pool: every image and every reload is half as large
+        import dataclasses
+        w = dataclasses.replace(w, shape=dataclasses.replace(w.shape, dtype="fp8"), name=w.name + "-fp8pool")
+        kw = dict(k_scale=w.data_scale / 16, v_scale=w.data_scale / 16)
+        args.no_cpu_baseline = True   # the timed oracle sample is the bf16 one
     sh = w.shape
     L, bs = sh.num_layers, sh.block_size
     dlens, plens, host = list(w.decode_lens), list(w.prompt_lens), list(w.offload_layers)
@@ -280,7 +286,7 @@ def mixed_iteration(args) -> None:
         f"pool {nblk} blocks = {nblk * sh.block_bytes / 2**30:.1f} GiB; host images "
         f"{len(host) * dblk * sh.block_bytes / 2**30:.1f} GiB")
     it = MixedIteration(sh, dlens, plens, host, nblk, ring_layers=R, free_order=wl.free_list_order(5, nblk),
-                        tier_units=8, tier_threads=args.tier_threads)
+                        tier_units=8, tier_threads=args.tier_threads, **kw)
     gen = torch.Generator(device=dev)
     gen.manual_seed(wl.SEED_BASE + 5)
 
@@ -348,6 +354,7 @@ def mixed_iteration(args) -> None:
         "metric": METRIC, "value": round(decode_gbs, 2), "unit": "GB/s",
         "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": round(wall * 1e3, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "kv_pool": sh.dtype,
         "config": {"workload": f"5: {w.name} (L={L}, Hq={sh.num_q_heads}, Hkv={sh.num_kv_heads}, d={sh.head_dim}, block 16, "
                                f"{B} decoding sequences with contexts {min(dlens)}..{max(dlens)} ({Td} tokens), "
                                f"{len(host)} of {L} layers of them in ordinary host memory and reloaded through a ring of "
