@@ -13,6 +13,7 @@
 // exp(m_i - m) weights.
 
 #include "lkv_internal.hpp"
+#include <type_traits>
 
 namespace {
 
@@ -408,6 +409,22 @@ __device__ __forceinline__ u32x4 widen_e4m3(u32x2 w) {
                __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w.y, 1.0f, true))};
 }
 
+// What a lane loads per access: 16 bytes = 8 bf16 channels, or 8 bytes = 8 E4M3 codes.
+// The lane's 8 key channels of product step kk as bf16: bf16 keys are loaded one step per load, 8-bit keys two.
+template <bool FP8> __device__ __forceinline__ u32x4 key_piece(const u32x4 *k, int kk) {
+  if constexpr (FP8) {
+    const u32x4 w = k[kk >> 1];
+    return (kk & 1) ? widen_e4m3(u32x2{w.z, w.w}) : widen_e4m3(u32x2{w.x, w.y});
+  } else {
+    return k[kk];
+  }
+}
+// Channels 2T, 2T+1 of a lane's 8 channels as one word of two bf16.
+template <int T> __device__ __forceinline__ unsigned bf16_pair(u32x4 w) { return w[T]; }
+template <int T> __device__ __forceinline__ unsigned bf16_pair(u32x2 w) {
+  return __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[T >> 1], 1.0f, (T & 1) != 0));
+}
+
 template <int G, int WAVES, bool FP8>
 __global__ void __launch_bounds__(WAVES * 64)
 paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, const char *__restrict__ pool,
@@ -422,6 +439,9 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
   constexpr int D = 128;
   constexpr int kRow = FP8 ? D : D * 2;  // bytes per key/value row
   constexpr int kPiece = FP8 ? 8 : 16;   // bytes of 8 channels
+  constexpr int kDepth = 2;              // block pairs in flight per wavefront
+  constexpr int kKeyLoads = FP8 ? 2 : 4; // 16-byte loads per key row and lane
+  using Piece = std::conditional_t<FP8, u32x2, u32x4>;
   const int Hkv = Hq / group;
   const int g = blockIdx.x % Hkv;  // kv head fastest: workgroups go round-robin to the XCDs
   int s = blockIdx.x / Hkv, part = 0;  // no context is split: one item per sequence
@@ -446,7 +466,10 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
     u32x4 w = {0, 0, 0, 0};
-    if (c < group) w = *(const u32x4 *)(Q + ((int64_t)s * Hq + g * group + c) * D + 32 * kk + 8 * hq);
+    // which 8 channels the lane holds in product step kk: any split of the 128 channels over (kk, hq) will do as
+    // long as keys and queries use the same one; the 8-bit layout lets a lane take 16 codes of a key with one load
+    const int ch = FP8 ? 64 * (kk >> 1) + 16 * hq + 8 * (kk & 1) : 32 * kk + 8 * hq;
+    if (c < group) w = *(const u32x4 *)(Q + ((int64_t)s * Hq + g * group + c) * D + ch);
     qop[kk] = __builtin_bit_cast(bf16x8, w);
   }
   f32x4 oacc[8];
@@ -459,7 +482,7 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
   const int my_pairs = wave < npairs ? (npairs - wave + WAVES - 1) / WAVES : 0;
   const int32_t *table = block_table + (int64_t)s * max_blocks;
   // byte offsets inside a (block, head) run for the two roles of this lane
-  const int k_off = (8 * ((c >> 2) & 1) + (c & 3)) * kRow + kPiece * hq;   // key row kappa_X(c) % 16, piece hq
+  const int k_off = (8 * ((c >> 2) & 1) + (c & 3)) * kRow + 16 * hq;       // key row kappa_X(c) % 16, 16 bytes at hq
   const int v_off = kBlock * kRow + 8 * (hq & 1) * kRow + kPiece * c;       // value rows 8*(hq%2)..+7, piece c
   const bool k_second = c >= 8, v_second = hq >= 2;                     // which block of the pair
   const int64_t head_off = (int64_t)g * (2 * kBlock * kRow);
@@ -472,7 +495,7 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
     // the result is wrong but nothing outside the pool is read; -1 marks "no second block" in a pair
     const int my_entry = (lane < 2 * cnt && bidx < nb_end) ? min(max(table[bidx], 0), pool_blocks - 1) : -1;
 
-    auto load = [&](int it, u32x4 *kx, u32x4 *ky, u32x4 *vr) {
+    auto load = [&](int it, u32x4 *kx, u32x4 *ky, Piece *vr) {
       const int id0 = __builtin_amdgcn_readlane(my_entry, 2 * it);
       int id1 = __builtin_amdgcn_readlane(my_entry, 2 * it + 1);
       if (id1 < 0) id1 = id0;  // odd block count: the pair's second half is fully masked
@@ -480,44 +503,20 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
       const char *b1 = pool + (int64_t)id1 * block_bytes + head_off;
       const char *kb = (k_second ? b1 : b0) + k_off;
       const char *vb = (v_second ? b1 : b0) + v_off;
-      if (FP8) {  // raw codes travel in the first two words; compute() widens them once they have arrived
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          const u32x2 r = *(const u32x2 *)(kb + 32 * kk), t = *(const u32x2 *)(kb + 4 * kRow + 32 * kk);
-          kx[kk] = u32x4{r.x, r.y, 0u, 0u};
-          ky[kk] = u32x4{t.x, t.y, 0u, 0u};
-        }
+      for (int j = 0; j < kKeyLoads; ++j) kx[j] = *(const u32x4 *)(kb + 64 * j);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const u32x2 r = *(const u32x2 *)(vb + j * kRow);
-          vr[j] = u32x4{r.x, r.y, 0u, 0u};
-        }
-        return;
-      }
+      for (int j = 0; j < kKeyLoads; ++j) ky[j] = *(const u32x4 *)(kb + 4 * kRow + 64 * j);
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) kx[kk] = *(const u32x4 *)(kb + 64 * kk);
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) ky[kk] = *(const u32x4 *)(kb + 4 * kRow + 64 * kk);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) vr[j] = *(const u32x4 *)(vb + j * kRow);
+      for (int j = 0; j < 8; ++j) vr[j] = *(const Piece *)(vb + j * kRow);
     };
-    auto compute = [&](int it, const u32x4 *kx_in, const u32x4 *ky_in, u32x4 *vr) {
-      u32x4 kx[4], ky[4];
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        kx[kk] = FP8 ? widen_e4m3(u32x2{kx_in[kk].x, kx_in[kk].y}) : kx_in[kk];
-        ky[kk] = FP8 ? widen_e4m3(u32x2{ky_in[kk].x, ky_in[kk].y}) : ky_in[kk];
-      }
-      if (FP8) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) vr[j] = widen_e4m3(u32x2{vr[j].x, vr[j].y});
-      }
+    auto compute = [&](int it, const u32x4 *kx, const u32x4 *ky, Piece *vr) {
       const int key0 = (nb_begin + 2 * (wave + (p0 + it) * WAVES)) * kBlock + 8 * hq;  // this lane's 8 keys
       f32x4 sx = {0.f, 0.f, 0.f, 0.f}, sy = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        sx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kx[kk]), qop[kk], sx, 0, 0, 0);
-        sy = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ky[kk]), qop[kk], sy, 0, 0, 0);
+      for (int kk = 0; kk < 4; ++kk) {  // 8-bit codes are widened piece by piece, right before their product
+        sx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, key_piece<FP8>(kx, kk)), qop[kk], sx, 0, 0, 0);
+        sy = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, key_piece<FP8>(ky, kk)), qop[kk], sy, 0, 0, 0);
       }
       float t[8];
 #pragma unroll
@@ -546,27 +545,45 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
       const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
 #pragma unroll
       for (int j = 0; j < 8; ++j)
-        if (key0 + j >= end) vr[j] = u32x4{0, 0, 0, 0};
-      // 8x8 transpose of 16-bit elements: channel pair i/2 of key rows 2w, 2w+1 -> word w of patch row i
+        if (key0 + j >= end) vr[j] = Piece{};  // a masked slot may hold anything (the zero code is 0.0)
+      // 8x8 transpose of 16-bit elements: channel pair t of key rows 2w, 2w+1 -> word w of patch rows 2t, 2t+1
+      auto channel_pair = [&](auto tc) {
+        constexpr int T = decltype(tc)::value;
+        unsigned word[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const unsigned sel = (i & 1) ? 0x07060302u : 0x05040100u;
-        u32x4 a;
+        for (int j = 0; j < 8; ++j) word[j] = bf16_pair<T>(vr[j]);
 #pragma unroll
-        for (int w = 0; w < 4; ++w) a[w] = __builtin_amdgcn_perm(vr[2 * w + 1][i >> 1], vr[2 * w][i >> 1], sel);
-        oacc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), pb, oacc[i], 0, 0, 0);
-      }
+        for (int i = 2 * T; i < 2 * T + 2; ++i) {
+          const unsigned sel = (i & 1) ? 0x07060302u : 0x05040100u;
+          u32x4 a;
+#pragma unroll
+          for (int w = 0; w < 4; ++w) a[w] = __builtin_amdgcn_perm(word[2 * w + 1], word[2 * w], sel);
+          oacc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), pb, oacc[i], 0, 0, 0);
+        }
+      };
+      channel_pair(std::integral_constant<int, 0>{});
+      channel_pair(std::integral_constant<int, 1>{});
+      channel_pair(std::integral_constant<int, 2>{});
+      channel_pair(std::integral_constant<int, 3>{});
     };
 
-    // two block pairs in flight per wavefront: the next pair's loads are issued before the current pair's math
-    u32x4 kxa[4], kya[4], va[8], kxb[4], kyb[4], vb[8];
-    load(0, kxa, kya, va);
-    for (int it = 0; it < cnt; it += 2) {
-      if (it + 1 < cnt) load(it + 1, kxb, kyb, vb);
-      compute(it, kxa, kya, va);
-      if (it + 1 < cnt) {
-        if (it + 2 < cnt) load(it + 2, kxa, kya, va);
-        compute(it + 1, kxb, kyb, vb);
+    // kDepth block pairs in flight per wavefront: the loads of pair it + kDepth - 1 are issued before the math of
+    // pair it.  Measured: three pairs of bf16 do not fit the registers (spills, 40 % slower); three or four pairs of
+    // 8-bit codes fit and change nothing (what bounds the 8-bit kernel is the number of load instructions: taking a
+    // key's codes 16 bytes at a time instead of 8 gave 8-12 %).
+    u32x4 kxb[kDepth][kKeyLoads], kyb[kDepth][kKeyLoads];
+    Piece vb[kDepth][8];
+#pragma unroll
+    for (int d = 0; d < kDepth - 1; ++d)
+      if (d < cnt) load(d, kxb[d], kyb[d], vb[d]);
+    for (int it = 0; it < cnt; it += kDepth) {
+#pragma unroll
+      for (int d = 0; d < kDepth; ++d) {
+        if (it + d < cnt) {
+          constexpr int kAhead = kDepth - 1;
+          if (it + d + kAhead < cnt) load(it + d + kAhead, kxb[(d + kAhead) % kDepth], kyb[(d + kAhead) % kDepth], vb[(d + kAhead) % kDepth]);
+          compute(it + d, kxb[d], kyb[d], vb[d]);
+        }
       }
     }
   }
