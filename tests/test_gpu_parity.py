@@ -241,6 +241,33 @@ def test_group_sizes_that_are_not_powers_of_two(Hq, Hkv, d, dtype, partition):
     sc.close()
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_seeded_random_shapes(seed):
+    """Shapes nobody chose by hand: dtype, head_dim, kv heads, query heads per kv head, batch, lengths (two in five from
+    the values next to block, unit and tile boundaries), partition size and mask all drawn from the seed; the whole
+    flow of one layer against the oracle."""
+    rng = np.random.default_rng(7000 + seed)
+    special = [1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257]
+    dtype = str(rng.choice(["bf16", "bf16", "f32"]))
+    d = int(rng.choice([64, 128]))
+    Hkv = int(rng.choice([1, 2, 3, 4, 8]))
+    group = int(rng.integers(1, (16 if dtype == "bf16" and d == 128 else 8) + 1))
+    B = int(rng.integers(1, 9))
+    lens = tuple(int(rng.choice(special)) if rng.random() < 0.4 else int(rng.integers(1, 700)) for _ in range(B))
+    partition = int(rng.choice([0, 0, 64, 128, 256]))
+    causal = bool(rng.random() < 0.8)
+    shape = wl.KVShape(1, Hkv * group, Hkv, d, 16, dtype)
+    nblk = sum(wl.blocks_for(n + 2, 16) for n in lens) + 4
+    sc = Scenario(20 + seed % 5, shape, lens, nblk, decode_partition=partition)
+    sc.prefill_layer(0, causal=causal)
+    sc.check_pool("after prefill")
+    images = sc.offload_layer(0)
+    sc.reload_layer(0, images, order=list(reversed(range(B))))
+    sc.decode_step(0)
+    sc.decode_step(0, step=1, append=False)
+    sc.close()
+
+
 def test_decode_refuses_more_query_heads_per_kv_head_than_the_kernels_hold():
     for Hq, d, dtype in ((17, 128, "bf16"), (9, 64, "bf16"), (9, 128, "f32")):
         shape = wl.KVShape(1, Hq, 1, d, 16, dtype)
