@@ -37,7 +37,8 @@ def same_tokens(a, b, lens, sh) -> bool:
     return off == a.shape[0]
 
 
-def test_mixed_iteration_host_layers_through_a_ring_of_blocks_and_the_pageable_tier():
+@pytest.mark.parametrize("ring,unit_blocks,units,threads", [(2, 8, 3, 2), (1, 1, 1, 1), (3, 64, 8, 4)])
+def test_mixed_iteration_host_layers_through_a_ring_of_blocks_and_the_pageable_tier(ring, unit_blocks, units, threads):
     sh = wl.KVShape(6, 8, 4, 128, 16, "bf16")
     L, bs = sh.num_layers, sh.block_size
     dlens = [37, 500, 1200, 64, 333, 1999, 16]
@@ -48,11 +49,11 @@ def test_mixed_iteration_host_layers_through_a_ring_of_blocks_and_the_pageable_t
     assert retained == [2, 5]
     dblk = sum(wl.blocks_for(n, bs) for n in dlens)
     pblk = sum(wl.blocks_for(n, bs) for n in plens)
-    nblk = (len(retained) + 2) * dblk + L * pblk + 8      # retained layers + a ring of two + the prompts
+    nblk = (len(retained) + ring) * dblk + L * pblk + 8   # retained layers + the ring + the prompts
     order = wl.free_list_order(5, nblk, index=9)
     pool = H.zero_pool(sh, nblk)
-    it = MixedIteration(sh, dlens, plens, host, nblk, ring_layers=2, free_order=order, pool=pool,
-                        tier_unit_bytes=8 * sh.block_bytes, tier_units=3, tier_threads=2)
+    it = MixedIteration(sh, dlens, plens, host, nblk, ring_layers=ring, free_order=order, pool=pool,
+                        tier_unit_bytes=unit_blocks * sh.block_bytes, tier_units=units, tier_threads=threads)
     c = it.ctx
     o = orc.LayerKVOracle(L, sh.num_q_heads, sh.num_kv_heads, sh.head_dim, bs, L * (dblk + pblk), "bf16")
     scale = 0.5
