@@ -324,7 +324,9 @@ lkv_status lkv_set_link_gate(lkv_ctx *ctx, lkv_link_busy_fn busy, void *user, in
  * sequence s attends to positions 0..context_lens[s]-1; a zero context gives a zero row.
  * Waits (on `stream`) for LKV_EV_RELOADED of the layer.  Long contexts are split into
  * partitions whose partial results are merged by a second kernel; the split-K workspace is
- * grown with hipMalloc when a call needs more than any earlier one. */
+ * grown with hipMalloc when a call needs more than any earlier one.  A context has ONE workspace:
+ * split calls of one context must not run at the same time on different streams (calls on one stream,
+ * or ordered by events, are fine). */
 lkv_status lkv_paged_decode_attention(lkv_ctx *ctx, int32_t layer, const void *Q, void *O,
                                       const int32_t *block_table, int32_t max_blocks_per_seq,
                                       const int32_t *context_lens, int32_t num_seqs, void *stream);
