@@ -45,6 +45,8 @@ def parse_args():
                          "decode sequences)")
     ap.add_argument("--decode-seqs", type=int, default=64, help="workload 5: decoding sequences (64 = the full size)")
     ap.add_argument("--ring-layers", type=int, default=3, help="workload 5: sets of blocks the host layers pass through")
+    ap.add_argument("--tier-unit-mib", type=int, default=64, help="workload 5: size of one unit of the pinned ring")
+    ap.add_argument("--tier-units", type=int, default=4, help="workload 5: units in the pinned ring")
     ap.add_argument("--tier-threads", type=int, default=8,
                     help="workload 5: CPU threads that copy between the pinned ring and ordinary host memory")
     ap.add_argument("--kv-dtype", default="bf16", choices=("bf16", "fp8"),
@@ -286,7 +288,8 @@ def mixed_iteration(args) -> None:
         f"pool {nblk} blocks = {nblk * sh.block_bytes / 2**30:.1f} GiB; host images "
         f"{len(host) * dblk * sh.block_bytes / 2**30:.1f} GiB")
     it = MixedIteration(sh, dlens, plens, host, nblk, ring_layers=R, free_order=wl.free_list_order(5, nblk),
-                        tier_units=8, tier_threads=args.tier_threads, **kw)
+                        tier_unit_bytes=args.tier_unit_mib << 20, tier_units=args.tier_units,
+                        tier_threads=args.tier_threads, **kw)
     gen = torch.Generator(device=dev)
     gen.manual_seed(wl.SEED_BASE + 5)
 
@@ -383,7 +386,7 @@ def mixed_iteration(args) -> None:
         },
         "memory": {"pool_GiB": round(nblk * sh.block_bytes / 2**30, 1),
                    "host_images_GiB": round((reload_bytes + offload_bytes) / 2**30, 1),
-                   "pinned_MiB": 8 * 32, "tier_threads": args.tier_threads, "build_cached_state_s": round(t_build, 1)},
+                   "pinned_MiB": args.tier_units * args.tier_unit_mib, "tier_threads": args.tier_threads, "build_cached_state_s": round(t_build, 1)},
         "decode_after_reload_equals_decode_before_offload": exact,
         "roofline": {"kernel": "paged_decode_mfma_kernel (lkv_paged_decode_attention)", "bound": "hbm",
                      "achieved": round(decode_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",

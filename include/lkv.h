@@ -283,7 +283,10 @@ lkv_status lkv_unpack_layer_blocks(lkv_ctx *ctx, int32_t layer, const int32_t *b
  * link through a small ring of pinned units owned by the library, and CPU threads of the library copy between
  * the ring and the caller's buffer, so pinned memory stays at num_units*unit_bytes however much KV is
  * offloaded.  The calling thread blocks while all ring units are in use (that is the back-pressure of a
- * bounded ring), never for the link or the memcpy of a unit it has already handed over. */
+ * bounded ring), never for the link or the memcpy of a unit it has already handed over.  The link copies of the
+ * units run on `stream`; their gather / scatter kernels run on a helper stream of the library (over two halves of
+ * the device staging, so that the kernel of one unit overlaps the copy of the other), ordered behind everything
+ * `stream` holds when the call is made; what the caller puts on `stream` after the call is ordered behind them. */
 
 /* Sets the ring's shape: unit_bytes per unit (rounded down to whole blocks, at least one block, at most the
  * device staging), num_units >= 1 units of pinned memory, threads >= 1 CPU threads.  Zero keeps the default

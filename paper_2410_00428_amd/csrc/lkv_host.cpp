@@ -65,6 +65,10 @@ lkv_status staging_create(lkv_ctx *c, lkv::Staging &st) {
   for (auto &e : st.slot_done) LKV_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
   LKV_HIP(c, hipEventCreateWithFlags(&st.buf_free, hipEventDisableTiming));
   for (auto &e : st.copy_done) LKV_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+  LKV_HIP(c, hipStreamCreateWithFlags(&st.aux, hipStreamNonBlocking));  // default priority
+  LKV_HIP(c, hipEventCreateWithFlags(&st.entry, hipEventDisableTiming));
+  for (auto &e : st.half_ready) LKV_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+  for (auto &e : st.half_free) LKV_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
   return LKV_OK;
 }
 
@@ -77,6 +81,12 @@ void staging_destroy(lkv::Staging &st) {
   if (st.buf_free) (void)hipEventDestroy(st.buf_free);
   for (auto &e : st.copy_done)
     if (e) (void)hipEventDestroy(e);
+  if (st.entry) (void)hipEventDestroy(st.entry);
+  for (auto &e : st.half_ready)
+    if (e) (void)hipEventDestroy(e);
+  for (auto &e : st.half_free)
+    if (e) (void)hipEventDestroy(e);
+  if (st.aux) (void)hipStreamDestroy(st.aux);
   st = lkv::Staging{};
 }
 
@@ -135,7 +145,8 @@ lkv_status tier_build(lkv_ctx *c, int64_t unit_bytes, int32_t units, int32_t thr
   if (threads <= 0) threads = 4;
   int64_t blocks = unit_bytes / c->block_bytes;
   if (blocks < 1) blocks = 1;
-  if (blocks > c->staging_blocks) blocks = c->staging_blocks;
+  // two units of device staging, so that the kernel of one unit and the link copy of the other overlap
+  if (blocks > c->staging_blocks / 2) blocks = c->staging_blocks / 2 > 0 ? c->staging_blocks / 2 : 1;
   if (c->tier.running()) {
     if (!c->tier.wait_all()) return fail(c, LKV_ERR_DEVICE, "host tier: waiting for a device copy failed");
     LKV_HIP(c, hipDeviceSynchronize());
@@ -668,6 +679,12 @@ lkv_status lkv_offload_layer_pageable(lkv_ctx *c, int32_t layer, const int32_t *
   hipStream_t s = (hipStream_t)stream;
   if (lkv_status st = wait_event(c, layer, LKV_EV_KV_WRITTEN, s)) return st;
   lkv::Staging &sg = c->d2h;
+  const bool two_halves = 2 * c->unit_blocks <= c->staging_blocks;  // else one unit at a time, as a staging chunk
+  // the gathers run on the helper stream, behind everything the caller's stream holds at this point and behind the
+  // last user of the staging buffer
+  LKV_HIP(c, hipEventRecord(sg.entry, s));
+  LKV_HIP(c, hipStreamWaitEvent(sg.aux, sg.entry, 0));
+  if (sg.buf_used) LKV_HIP(c, hipStreamWaitEvent(sg.aux, sg.buf_free, 0));
   for (int64_t first = 0; first < n; first += c->unit_blocks) {
     int64_t m = n - first < c->unit_blocks ? n - first : c->unit_blocks;
     link_gate(c);
@@ -677,28 +694,35 @@ lkv_status lkv_offload_layer_pageable(lkv_ctx *c, int32_t layer, const int32_t *
       c->tier.release(u);
       return st;
     };
+    const int h = two_halves ? (int)(sg.units_issued & 1) : 0;
+    char *half = sg.buf + (size_t)h * (size_t)(c->unit_blocks * c->block_bytes);
     int slot;
-    if (lkv_status st = stage_ids(c, sg, block_ids + first, m, s, &slot)) return fail_unit(st);
-    hipError_t e = sg.buf_used ? hipStreamWaitEvent(s, sg.buf_free, 0) : hipSuccess;
+    if (lkv_status st = stage_ids(c, sg, block_ids + first, m, sg.aux, &slot)) return fail_unit(st);
+    hipError_t e = sg.half_used[h] ? hipStreamWaitEvent(sg.aux, sg.half_free[h], 0) : hipSuccess;
     hipEvent_t t0 = nullptr;
     if (e == hipSuccess)
-      if (lkv_status st = timed_begin(c, s, &t0)) return fail_unit(st);
-    if (e == hipSuccess) e = lkv::launch_gather_blocks(c, sg.ids_dev + (size_t)slot * c->staging_blocks, m, sg.buf, s);
+      if (lkv_status st = timed_begin(c, sg.aux, &t0)) return fail_unit(st);
+    if (e == hipSuccess) e = lkv::launch_gather_blocks(c, sg.ids_dev + (size_t)slot * c->staging_blocks, m, half, sg.aux);
     if (e == hipSuccess)
-      if (lkv_status st = timed_end(c, s, t0, 2 * m * c->block_bytes, lkv_ctx::kTimedPack)) return fail_unit(st);
-    if (e == hipSuccess) e = hipEventRecord(sg.slot_done[slot], s);
+      if (lkv_status st = timed_end(c, sg.aux, t0, 2 * m * c->block_bytes, lkv_ctx::kTimedPack)) return fail_unit(st);
+    if (e == hipSuccess) e = hipEventRecord(sg.slot_done[slot], sg.aux);
+    if (e == hipSuccess) e = hipEventRecord(sg.half_ready[h], sg.aux);
     if (e == hipSuccess && first + m == n)
-      if (lkv_status st = record_event(c, layer, LKV_EV_PACKED, s)) return fail_unit(st);
+      if (lkv_status st = record_event(c, layer, LKV_EV_PACKED, sg.aux)) return fail_unit(st);
+    if (e == hipSuccess) e = hipStreamWaitEvent(s, sg.half_ready[h], 0);
     if (e == hipSuccess)
       if (lkv_status st = pace_copy(c, sg)) return fail_unit(st);
     if (e == hipSuccess)
-      e = hipMemcpyAsync(c->tier.unit_ptr(u), sg.buf, (size_t)(m * c->block_bytes), hipMemcpyDeviceToHost, s);
+      e = hipMemcpyAsync(c->tier.unit_ptr(u), half, (size_t)(m * c->block_bytes), hipMemcpyDeviceToHost, s);
     if (e == hipSuccess)
       if (lkv_status st = copy_issued(c, sg, s)) return fail_unit(st);
     if (e == hipSuccess) e = hipEventRecord(c->unit_ev[(size_t)u], s);
+    if (e == hipSuccess) e = hipEventRecord(sg.half_free[h], s);
     if (e == hipSuccess) e = hipEventRecord(sg.buf_free, s);
     if (e != hipSuccess) return fail_unit(fail(c, LKV_ERR_DEVICE, "lkv_offload_layer_pageable: %s", hipGetErrorString(e)));
+    sg.half_used[h] = true;
     sg.buf_used = true;
+    sg.units_issued += 1;
     lkv::HostTier::Job j = unit_job(c, u);
     j.dst = (char *)host_dst + first * c->block_bytes;
     j.src = c->tier.unit_ptr(u);
@@ -724,6 +748,11 @@ lkv_status lkv_reload_layer_pageable(lkv_ctx *c, int32_t layer, const int32_t *b
   if (!c->tier.wait_key(layer)) return fail(c, LKV_ERR_DEVICE, "host tier: waiting for a device copy failed");
   hipStream_t s = (hipStream_t)stream;
   lkv::Staging &sg = c->h2d;
+  const bool two_halves = 2 * c->unit_blocks <= c->staging_blocks;
+  // the scatters run on the helper stream, behind everything the caller's stream holds at this point
+  LKV_HIP(c, hipEventRecord(sg.entry, s));
+  LKV_HIP(c, hipStreamWaitEvent(sg.aux, sg.entry, 0));
+  if (sg.buf_used) LKV_HIP(c, hipStreamWaitEvent(s, sg.buf_free, 0));
   for (int64_t first = 0; first < n; first += c->unit_blocks) {
     int64_t m = n - first < c->unit_blocks ? n - first : c->unit_blocks;
     link_gate(c);
@@ -733,26 +762,35 @@ lkv_status lkv_reload_layer_pageable(lkv_ctx *c, int32_t layer, const int32_t *b
       return st;
     };
     c->tier.copy_parallel(c->tier.unit_ptr(u), (const char *)host_src + first * c->block_bytes, m * c->block_bytes);
+    const int h = two_halves ? (int)(sg.units_issued & 1) : 0;
+    char *half = sg.buf + (size_t)h * (size_t)(c->unit_blocks * c->block_bytes);
     int slot;
-    if (lkv_status st = stage_ids(c, sg, block_ids + first, m, s, &slot)) return fail_unit(st);
-    hipError_t e = sg.buf_used ? hipStreamWaitEvent(s, sg.buf_free, 0) : hipSuccess;
+    if (lkv_status st = stage_ids(c, sg, block_ids + first, m, sg.aux, &slot)) return fail_unit(st);
+    hipError_t e = sg.half_used[h] ? hipStreamWaitEvent(s, sg.half_free[h], 0) : hipSuccess;  // its last scatter
     if (e == hipSuccess)
       if (lkv_status st = pace_copy(c, sg)) return fail_unit(st);
     if (e == hipSuccess)
-      e = hipMemcpyAsync(sg.buf, c->tier.unit_ptr(u), (size_t)(m * c->block_bytes), hipMemcpyHostToDevice, s);
+      e = hipMemcpyAsync(half, c->tier.unit_ptr(u), (size_t)(m * c->block_bytes), hipMemcpyHostToDevice, s);
     if (e == hipSuccess)
       if (lkv_status st = copy_issued(c, sg, s)) return fail_unit(st);
     if (e == hipSuccess) e = hipEventRecord(c->unit_ev[(size_t)u], s);
+    if (e == hipSuccess) e = hipEventRecord(sg.half_ready[h], s);
     if (e != hipSuccess) return fail_unit(fail(c, LKV_ERR_DEVICE, "lkv_reload_layer_pageable: %s", hipGetErrorString(e)));
     c->tier.submit(unit_job(c, u));  // the unit is free again once the link copy has read it
+    LKV_HIP(c, hipStreamWaitEvent(sg.aux, sg.half_ready[h], 0));
     hipEvent_t t0;
-    if (lkv_status st = timed_begin(c, s, &t0)) return st;
-    LKV_HIP(c, lkv::launch_scatter_blocks(c, sg.ids_dev + (size_t)slot * c->staging_blocks, m, sg.buf, s));
-    if (lkv_status st = timed_end(c, s, t0, 2 * m * c->block_bytes, lkv_ctx::kTimedUnpack)) return st;
-    LKV_HIP(c, hipEventRecord(sg.slot_done[slot], s));
-    LKV_HIP(c, hipEventRecord(sg.buf_free, s));
+    if (lkv_status st = timed_begin(c, sg.aux, &t0)) return st;
+    LKV_HIP(c, lkv::launch_scatter_blocks(c, sg.ids_dev + (size_t)slot * c->staging_blocks, m, half, sg.aux));
+    if (lkv_status st = timed_end(c, sg.aux, t0, 2 * m * c->block_bytes, lkv_ctx::kTimedUnpack)) return st;
+    LKV_HIP(c, hipEventRecord(sg.slot_done[slot], sg.aux));
+    LKV_HIP(c, hipEventRecord(sg.half_free[h], sg.aux));
+    LKV_HIP(c, hipEventRecord(sg.buf_free, sg.aux));
+    sg.half_used[h] = true;
     sg.buf_used = true;
+    sg.units_issued += 1;
   }
+  // what the caller puts on its stream after this call finds the blocks written
+  if (n > 0) LKV_HIP(c, hipStreamWaitEvent(s, sg.buf_free, 0));
   c->stats.pageable_reload_calls += 1;
   c->stats.pageable_reload_bytes += n * c->block_bytes;
   return record_event(c, layer, LKV_EV_RELOADED, s);

@@ -43,6 +43,14 @@ struct Staging {
   static constexpr int kCopyRing = 4, kMaxInFlight = 2;
   hipEvent_t copy_done[kCopyRing] = {};
   int64_t copies_issued = 0;
+  // The pageable calls move a layer in many small units.  With the gather (or scatter) kernel of a unit on the
+  // caller's stream the link would idle between two copies while the kernel runs and the queues hand over; so the
+  // kernels run on a helper stream, over the two halves of buf in turn, and only events connect them to the copies.
+  hipStream_t aux = nullptr;
+  hipEvent_t entry = nullptr;             // the caller's stream at the start of a call: the helper stream starts after it
+  hipEvent_t half_ready[2] = {}, half_free[2] = {};  // gather done / copy done (offload); copy done / scatter done (reload)
+  bool half_used[2] = {false, false};
+  int64_t units_issued = 0;               // picks the half
 };
 
 }  // namespace lkv
