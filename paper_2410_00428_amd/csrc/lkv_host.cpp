@@ -67,8 +67,7 @@ lkv_status staging_create(lkv_ctx *c, lkv::Staging &st) {
   for (auto &e : st.copy_done) LKV_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
   LKV_HIP(c, hipStreamCreateWithFlags(&st.aux, hipStreamNonBlocking));  // default priority
   LKV_HIP(c, hipEventCreateWithFlags(&st.entry, hipEventDisableTiming));
-  for (auto &e : st.half_ready) LKV_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
-  for (auto &e : st.half_free) LKV_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+  for (auto &e : st.half_kernel) LKV_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
   return LKV_OK;
 }
 
@@ -82,9 +81,7 @@ void staging_destroy(lkv::Staging &st) {
   for (auto &e : st.copy_done)
     if (e) (void)hipEventDestroy(e);
   if (st.entry) (void)hipEventDestroy(st.entry);
-  for (auto &e : st.half_ready)
-    if (e) (void)hipEventDestroy(e);
-  for (auto &e : st.half_free)
+  for (auto &e : st.half_kernel)
     if (e) (void)hipEventDestroy(e);
   if (st.aux) (void)hipStreamDestroy(st.aux);
   st = lkv::Staging{};
@@ -118,6 +115,19 @@ lkv_status copy_issued(lkv_ctx *c, lkv::Staging &st, hipStream_t s) {
   return LKV_OK;
 }
 
+// The same pacing for the unit copies of the pageable calls, on the ring unit events (see Staging).
+lkv_status pace_unit_copy(lkv_ctx *c, lkv::Staging &st) {
+  if (st.copies_issued >= lkv::Staging::kMaxInFlight) {
+    hipEvent_t ev = st.unit_copies[(st.copies_issued - lkv::Staging::kMaxInFlight) % lkv::Staging::kCopyRing];
+    if (ev) LKV_HIP(c, hipEventSynchronize(ev));
+  }
+  return LKV_OK;
+}
+void unit_copy_issued(lkv::Staging &st, hipEvent_t unit_event) {
+  st.unit_copies[st.copies_issued % lkv::Staging::kCopyRing] = unit_event;
+  st.copies_issued += 1;
+}
+
 // Section 3.2.3: ask before every unit whether the link is taken by traffic that must not be delayed.
 void link_gate(lkv_ctx *c) {
   if (!c->gate_busy) return;
@@ -127,8 +137,15 @@ void link_gate(lkv_ctx *c) {
   }
 }
 
-void tier_destroy(lkv_ctx *c) {
+void tier_destroy(lkv_ctx *c) {  // the device is idle when this is called
   c->tier.stop();
+  for (lkv::Staging *sg : {&c->d2h, &c->h2d}) {  // forget the ring unit events that are destroyed below
+    for (auto &e : sg->unit_copies) e = nullptr;
+    for (int h = 0; h < 2; ++h) {
+      sg->half_copy[h] = nullptr;
+      sg->half_used[h] = false;
+    }
+  }
   for (auto &e : c->unit_ev)
     if (e) (void)hipEventDestroy(e);
   c->unit_ev.clear();
@@ -698,7 +715,7 @@ lkv_status lkv_offload_layer_pageable(lkv_ctx *c, int32_t layer, const int32_t *
     char *half = sg.buf + (size_t)h * (size_t)(c->unit_blocks * c->block_bytes);
     int slot;
     if (lkv_status st = stage_ids(c, sg, block_ids + first, m, sg.aux, &slot)) return fail_unit(st);
-    hipError_t e = sg.half_used[h] ? hipStreamWaitEvent(sg.aux, sg.half_free[h], 0) : hipSuccess;
+    hipError_t e = sg.half_used[h] ? hipStreamWaitEvent(sg.aux, sg.half_copy[h], 0) : hipSuccess;
     hipEvent_t t0 = nullptr;
     if (e == hipSuccess)
       if (lkv_status st = timed_begin(c, sg.aux, &t0)) return fail_unit(st);
@@ -706,20 +723,19 @@ lkv_status lkv_offload_layer_pageable(lkv_ctx *c, int32_t layer, const int32_t *
     if (e == hipSuccess)
       if (lkv_status st = timed_end(c, sg.aux, t0, 2 * m * c->block_bytes, lkv_ctx::kTimedPack)) return fail_unit(st);
     if (e == hipSuccess) e = hipEventRecord(sg.slot_done[slot], sg.aux);
-    if (e == hipSuccess) e = hipEventRecord(sg.half_ready[h], sg.aux);
+    if (e == hipSuccess) e = hipEventRecord(sg.half_kernel[h], sg.aux);
     if (e == hipSuccess && first + m == n)
       if (lkv_status st = record_event(c, layer, LKV_EV_PACKED, sg.aux)) return fail_unit(st);
-    if (e == hipSuccess) e = hipStreamWaitEvent(s, sg.half_ready[h], 0);
+    if (e == hipSuccess) e = hipStreamWaitEvent(s, sg.half_kernel[h], 0);
     if (e == hipSuccess)
-      if (lkv_status st = pace_copy(c, sg)) return fail_unit(st);
+      if (lkv_status st = pace_unit_copy(c, sg)) return fail_unit(st);
     if (e == hipSuccess)
       e = hipMemcpyAsync(c->tier.unit_ptr(u), half, (size_t)(m * c->block_bytes), hipMemcpyDeviceToHost, s);
-    if (e == hipSuccess)
-      if (lkv_status st = copy_issued(c, sg, s)) return fail_unit(st);
     if (e == hipSuccess) e = hipEventRecord(c->unit_ev[(size_t)u], s);
-    if (e == hipSuccess) e = hipEventRecord(sg.half_free[h], s);
-    if (e == hipSuccess) e = hipEventRecord(sg.buf_free, s);
+    if (e == hipSuccess && first + m == n) e = hipEventRecord(sg.buf_free, s);
     if (e != hipSuccess) return fail_unit(fail(c, LKV_ERR_DEVICE, "lkv_offload_layer_pageable: %s", hipGetErrorString(e)));
+    unit_copy_issued(sg, c->unit_ev[(size_t)u]);
+    sg.half_copy[h] = c->unit_ev[(size_t)u];
     sg.half_used[h] = true;
     sg.buf_used = true;
     sg.units_issued += 1;
@@ -766,25 +782,23 @@ lkv_status lkv_reload_layer_pageable(lkv_ctx *c, int32_t layer, const int32_t *b
     char *half = sg.buf + (size_t)h * (size_t)(c->unit_blocks * c->block_bytes);
     int slot;
     if (lkv_status st = stage_ids(c, sg, block_ids + first, m, sg.aux, &slot)) return fail_unit(st);
-    hipError_t e = sg.half_used[h] ? hipStreamWaitEvent(s, sg.half_free[h], 0) : hipSuccess;  // its last scatter
+    hipError_t e = sg.half_used[h] ? hipStreamWaitEvent(s, sg.half_kernel[h], 0) : hipSuccess;  // its last scatter
     if (e == hipSuccess)
-      if (lkv_status st = pace_copy(c, sg)) return fail_unit(st);
+      if (lkv_status st = pace_unit_copy(c, sg)) return fail_unit(st);
     if (e == hipSuccess)
       e = hipMemcpyAsync(half, c->tier.unit_ptr(u), (size_t)(m * c->block_bytes), hipMemcpyHostToDevice, s);
-    if (e == hipSuccess)
-      if (lkv_status st = copy_issued(c, sg, s)) return fail_unit(st);
     if (e == hipSuccess) e = hipEventRecord(c->unit_ev[(size_t)u], s);
-    if (e == hipSuccess) e = hipEventRecord(sg.half_ready[h], s);
+    if (e == hipSuccess) e = hipStreamWaitEvent(sg.aux, c->unit_ev[(size_t)u], 0);
     if (e != hipSuccess) return fail_unit(fail(c, LKV_ERR_DEVICE, "lkv_reload_layer_pageable: %s", hipGetErrorString(e)));
+    unit_copy_issued(sg, c->unit_ev[(size_t)u]);
     c->tier.submit(unit_job(c, u));  // the unit is free again once the link copy has read it
-    LKV_HIP(c, hipStreamWaitEvent(sg.aux, sg.half_ready[h], 0));
     hipEvent_t t0;
     if (lkv_status st = timed_begin(c, sg.aux, &t0)) return st;
     LKV_HIP(c, lkv::launch_scatter_blocks(c, sg.ids_dev + (size_t)slot * c->staging_blocks, m, half, sg.aux));
     if (lkv_status st = timed_end(c, sg.aux, t0, 2 * m * c->block_bytes, lkv_ctx::kTimedUnpack)) return st;
     LKV_HIP(c, hipEventRecord(sg.slot_done[slot], sg.aux));
-    LKV_HIP(c, hipEventRecord(sg.half_free[h], sg.aux));
-    LKV_HIP(c, hipEventRecord(sg.buf_free, sg.aux));
+    LKV_HIP(c, hipEventRecord(sg.half_kernel[h], sg.aux));
+    if (first + m == n) LKV_HIP(c, hipEventRecord(sg.buf_free, sg.aux));
     sg.half_used[h] = true;
     sg.buf_used = true;
     sg.units_issued += 1;

@@ -48,9 +48,16 @@ struct Staging {
   // kernels run on a helper stream, over the two halves of buf in turn, and only events connect them to the copies.
   hipStream_t aux = nullptr;
   hipEvent_t entry = nullptr;             // the caller's stream at the start of a call: the helper stream starts after it
-  hipEvent_t half_ready[2] = {}, half_free[2] = {};  // gather done / copy done (offload); copy done / scatter done (reload)
+  // Between two link copies the caller's stream carries one wait and one event record, no more (every packet
+  // between two copies costs link time): the event of the ring unit a copy goes to or comes from serves the worker
+  // threads, the pacing and the other stream.  Offload: half_kernel[h] = gather into half h done (helper stream),
+  // half_copy[h] = the ring unit event of the last copy out of half h.  Reload: half_copy[h] = the ring unit event of
+  // the last copy into half h, half_kernel[h] = scatter out of half h done (helper stream).
+  hipEvent_t half_kernel[2] = {};
+  hipEvent_t half_copy[2] = {};           // not owned: handles of ring unit events
   bool half_used[2] = {false, false};
   int64_t units_issued = 0;               // picks the half
+  hipEvent_t unit_copies[kCopyRing] = {}; // not owned: the ring unit events of the last copies, for the pacing
 };
 
 }  // namespace lkv
