@@ -98,7 +98,7 @@ class MixedIteration:
                 c.stream_wait_event(l, lkv.LKV_EV_PACKED, self.main)            # the blocks are reused below
                 c.stream_wait_event(l, lkv.LKV_EV_PACKED, self.h2d)
                 self._free_decode(l)
-            torch.cuda.current_stream().synchronize()                            # slots_dev, K, V may go
+            self.main.synchronize()                                              # slots_dev, K, V may go
             progress(f"cached layer {l}" + (" -> host" if l in self.host_layers else ""))
         c.host_tier_synchronize(-1)
         for l in self.host_layers:
