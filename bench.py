@@ -445,10 +445,10 @@ def main():
     layer_bytes = sum(wl.blocks_for(n, sh.block_size) for n in w.prompt_lens) * sh.block_bytes
     pinned = {l: eng.pinned(layer_bytes) for l in off_layers}
 
-    def step():
+    def step(after_layer=None):
         eng.reset()
         eng.begin_prompts(w.prompt_lens)
-        eng.prefill_all_layers(Qs, Ks, Vs, O, pinned)
+        eng.prefill_all_layers(Qs, Ks, Vs, O, pinned, after_layer)
         for l in off_layers:
             eng.release_offloaded(l)
         for l in off_layers:
@@ -475,9 +475,20 @@ def main():
     eng.ctx.set_profiling(False)
     eng.timing = True
     eng.timers.clear()
-    step()
+    # in this extra step a one-wavefront kernel behind every layer's attention launch reads the shader clock (two
+    # samples ~20 us apart), to show what the power management makes of the prefill burst
+    clk_buf = torch.zeros(L, 4, dtype=torch.int64, device=dev)
+    clk_khz = []
+    step(lambda l: clk_khz.append(eng.ctx.probe_clock_trace(clk_buf[l], 2, 40000, eng.main)))
     ms = eng.elapsed_ms()
     eng.timing = False
+    clk = clk_buf.cpu().numpy()
+    clk_mhz = (clk[:, 3] - clk[:, 1]) / np.maximum(clk[:, 2] - clk[:, 0], 1) * (clk_khz[0] / 1000.0)
+    clock_trace = {"after_layer_MHz": [round(float(x)) for x in clk_mhz],
+                   "min_MHz": round(float(clk_mhz.min())), "median_MHz": round(float(np.median(clk_mhz))),
+                   "prefill_us_per_layer": [round(x * 1e3) for x in ms.get("prefill_attention", [])],
+                   "note": "lkv_probe_clock_trace behind every layer's attention launch of one extra step: shader "
+                           "cycles per tick of the constant-rate clock over ~20 us"}
 
     K = args.steps
     def total(name):
@@ -748,6 +759,7 @@ def main():
                          "note": "lkv_probe_mfma_rate: nothing but v_mfma_f32_32x32x16_bf16 for 30 ms, two wavefronts "
                                  "per SIMD; the clock under a matrix load depends on the operand bits, so the published "
                                  "2.5 PFLOP/s (2.4 GHz) is not reachable with real data on this box"}},
+        "shader_clock_during_step": clock_trace,
         "rooflines_other": {
             "decode": {"bound": "hbm", "achieved": round(decode_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                        "frac": round(decode_gbs / HBM_PEAK_GBS, 4)},

@@ -355,6 +355,13 @@ lkv_status lkv_get_stats(lkv_ctx *ctx, lkv_stats *out, int64_t size);
  * operand bits toggle.  Blocks the host; allocates and frees a few bytes of device memory. */
 lkv_status lkv_probe_mfma_rate(lkv_ctx *ctx, double millis, int32_t random_operands, double *tflops,
                                double *clock_mhz, void *stream);
+/* Measurement helper: enqueues on `stream` one wavefront that writes n pairs (tick of the constant-rate clock,
+ * shader cycle count) to out (device, 2*n int64), about gap_cycles shader cycles apart, and exits; returns at once.
+ * *wall_clock_khz (host) = rate of the constant-rate clock.  The shader clock between two samples is
+ * (cycles[i+1]-cycles[i]) / (ticks[i+1]-ticks[i]) * wall_clock_khz: put next to work on another stream it shows what
+ * the power management makes of that load.  1 <= n <= 1 << 20, 0 <= gap_cycles <= 1 << 24. */
+lkv_status lkv_probe_clock_trace(lkv_ctx *ctx, int64_t *out, int32_t n, int32_t gap_cycles, int32_t *wall_clock_khz,
+                                 void *stream);
 
 #ifdef __cplusplus
 }

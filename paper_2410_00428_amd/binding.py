@@ -35,7 +35,7 @@ EXPORTS = (
     "lkv_host_tier_config", "lkv_offload_layer_pageable", "lkv_reload_layer_pageable", "lkv_host_tier_synchronize",
     "lkv_set_link_gate",
     "lkv_stream_wait_event", "lkv_event_synchronize", "lkv_set_profiling", "lkv_get_stats",
-    "lkv_probe_mfma_rate",
+    "lkv_probe_mfma_rate", "lkv_probe_clock_trace",
     "lkv_prefill_time", "lkv_offload_time", "lkv_plan_offload", "lkv_allow_prefill_time", "lkv_max_prefills",
     "lkv_forecast_avail", "lkv_pressure_offload",
 )
@@ -133,6 +133,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "lkv_set_profiling": (i32, [vp, i32]),
         "lkv_get_stats": (i32, [vp, P(LkvStats), i64]),
         "lkv_probe_mfma_rate": (i32, [vp, ctypes.c_double, i32, P(ctypes.c_double), P(ctypes.c_double), vp]),
+        "lkv_probe_clock_trace": (i32, [vp, vp, i32, i32, P(i32), vp]),
         "lkv_prefill_time": (ctypes.c_double, [P(CostModel), i64]),
         "lkv_offload_time": (ctypes.c_double, [P(CostModel), i64, i32]),
         "lkv_plan_offload": (i32, [P(CostModel), i64, P(i32), vp]),
@@ -402,6 +403,13 @@ class LKV:
         self._check(self.lib.lkv_probe_mfma_rate(self.h, float(millis), int(bool(random_operands)), ctypes.byref(tf),
                                                  ctypes.byref(mhz), _stream(stream)))
         return tf.value, mhz.value
+
+    def probe_clock_trace(self, out, n: int, gap_cycles: int = 100000, stream=None) -> int:
+        """Enqueues the clock sampler (n pairs of tick, shader cycles into ``out``: device, 2*n int64); returns the
+        tick rate in kHz.  Marshalling only: turning the pairs into MHz is the caller's."""
+        khz = ctypes.c_int32(0)
+        self._check(self.lib.lkv_probe_clock_trace(self.h, _ptr(out), n, gap_cycles, ctypes.byref(khz), _stream(stream)))
+        return khz.value
 
     def get_stats(self) -> dict:
         s = LkvStats()

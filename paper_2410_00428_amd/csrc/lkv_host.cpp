@@ -880,6 +880,19 @@ lkv_status lkv_probe_mfma_rate(lkv_ctx *c, double millis, int32_t random_operand
   return LKV_OK;
 }
 
+lkv_status lkv_probe_clock_trace(lkv_ctx *c, int64_t *out, int32_t n, int32_t gap_cycles, int32_t *wall_clock_khz,
+                                 void *stream) {
+  if (!c || !out || !wall_clock_khz) return LKV_ERR_INVALID_ARG;
+  if (c->logical_only) return fail(c, LKV_ERR_DEVICE, "lkv_probe_clock_trace: this context has no device resources");
+  if (n < 1 || n > (1 << 20) || gap_cycles < 0 || gap_cycles > (1 << 24))
+    return fail(c, LKV_ERR_INVALID_ARG, "lkv_probe_clock_trace: n or gap_cycles out of range");
+  LKV_HIP(c, hipSetDevice(c->device));
+  int khz = 0;
+  LKV_HIP(c, lkv::probe_clock_trace((long long *)out, n, gap_cycles, &khz, (hipStream_t)stream));
+  *wall_clock_khz = khz;
+  return LKV_OK;
+}
+
 lkv_status lkv_get_stats(lkv_ctx *c, lkv_stats *out, int64_t size) {
   if (!c || !out || size < 0) return LKV_ERR_INVALID_ARG;
   if (lkv_status st = fold_timed(c, true)) return st;

@@ -56,9 +56,30 @@ __global__ void __launch_bounds__(256) mfma_stream_kernel(float *sink, long long
   }
 }
 
+// One wavefront writes n pairs (constant-rate clock, shader cycle counter), about `gap` shader cycles apart, and
+// exits: next to another stream's work it shows what the shader clock does under that load.  Every wait is bounded.
+__global__ void __launch_bounds__(64) clock_trace_kernel(long long *out, int n, int gap) {
+  if (threadIdx.x != 0) return;
+  for (int i = 0; i < n; ++i) {
+    out[2 * i] = __builtin_amdgcn_s_memrealtime();
+    out[2 * i + 1] = __builtin_readcyclecounter();
+    const long long c0 = __builtin_readcyclecounter();
+    for (int guard = 0; guard < 100000 && __builtin_readcyclecounter() - c0 < gap; ++guard) __builtin_amdgcn_s_sleep(64);
+  }
+}
+
 }  // namespace
 
 namespace lkv {
+
+hipError_t probe_clock_trace(long long *out_dev, int n, int gap_cycles, int *wall_khz, hipStream_t s) {
+  int dev = 0;
+  hipError_t e;
+  if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+  if ((e = hipDeviceGetAttribute(wall_khz, hipDeviceAttributeWallClockRate, dev)) != hipSuccess) return e;
+  hipLaunchKernelGGL(clock_trace_kernel, dim3(1), dim3(64), 0, s, out_dev, n, gap_cycles);
+  return hipGetLastError();
+}
 
 hipError_t probe_mfma_rate(double millis, int random_operands, double *tflops, double *clock_mhz, hipStream_t s) {
   int cus = 0, wall_khz = 0;

@@ -96,15 +96,18 @@ class LayerKVEngine:
         slots_dev = torch.from_numpy(self.map_prefill_layer(layer)).to(self.device)
         self.launch_prefill_layer(layer, Q, K, V, O, slots_dev, offload_to, attention)
 
-    def prefill_all_layers(self, Qs, Ks, Vs, O, offload: Dict[int, torch.Tensor]) -> None:
+    def prefill_all_layers(self, Qs, Ks, Vs, O, offload: Dict[int, torch.Tensor], after_layer=None) -> None:
         """All layers of a prompt batch: the host-side mapping of every layer first (one upload), then the
-        kernels of all layers back to back, each offloaded layer's copy starting behind its write."""
+        kernels of all layers back to back, each offloaded layer's copy starting behind its write.
+        ``after_layer(l)``, if given, is called when layer l's launches are queued (measurement hooks)."""
         L = self.shape.num_layers
         slots = np.stack([self.map_prefill_layer(l) for l in range(L)])
         slots_dev = torch.from_numpy(slots).to(self.device)
         for l in range(L):
             i = l % len(Qs)
             self.launch_prefill_layer(l, Qs[i], Ks[i], Vs[i], O, slots_dev[l], offload.get(l))
+            if after_layer is not None:
+                after_layer(l)
         self._keep_prefill = slots_dev
 
     def layer_block_ids(self, layer: int) -> np.ndarray:

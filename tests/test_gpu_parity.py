@@ -490,6 +490,23 @@ def test_offload_on_side_stream_overlapping_next_layers_compute():
     sc.close()
 
 
+def test_clock_trace_is_monotonic_and_reads_a_plausible_shader_clock():
+    shape = wl.KVShape(1, 2, 2, 64, 16, "bf16")
+    c, o, pool = H.make_pair(shape, 4)
+    n = 64
+    out = torch.zeros(2 * n, dtype=torch.int64, device=H.DEV)
+    khz = c.probe_clock_trace(out, n, 20000)
+    torch.cuda.synchronize()
+    a = out.cpu().numpy().reshape(n, 2)
+    assert 1000 <= khz <= 1000000
+    assert (np.diff(a[:, 0]) > 0).all() and (np.diff(a[:, 1]) > 0).all()
+    mhz = np.diff(a[:, 1]) / np.diff(a[:, 0]) * (khz / 1000.0)
+    assert 100.0 < np.median(mhz) < 3000.0, mhz
+    with pytest.raises(lkv.LkvError):
+        c.probe_clock_trace(out, 0, 20000)
+    c.destroy()
+
+
 def test_mfma_probe_reports_a_plausible_rate_and_clock():
     """Measurement helper: the sustained MFMA rate equals 4 SIMDs x 1024 flop/clock x CUs x measured clock
     (the stream keeps the pipes full), and constant operands never run slower than random ones."""
