@@ -303,3 +303,66 @@ def test_mixed_length_prefill_batch_at_the_7b_head_count_sampled_rows():
     pairs = [(s, h) for s in range(len(lens)) for h in ((3 * s) % 32, 31 - s)]
     sampled_prefill_check(5, 3, Q, K, V, Od, lens, sh, 128 ** -0.5, pairs, rows_per=24)
     c.destroy()
+
+
+# ----------------------------------------------------------------------------- workload 5 through the ring
+def test_workload5_mixed_iteration_through_the_ring_at_the_7b_shape():
+    """The iteration ``bench.py --workload 5`` times, at the 7B shape with all 32 layers, 24 of them in ordinary host
+    memory behind a ring of three sets of blocks, the two 8192-token prompts prefilled and offloaded alongside - cut
+    to the first 8 of the 64 decoding sequences (contexts 3997..13049) for the CPU side's sake.  Checked against the
+    oracle on what it can compute one by one: decode rows of the shortest and the longest sequence in a retained and
+    two reloaded layers, sampled causal rows of the new prompts, the new prompts' offload image and a decoding
+    sequence's stretch of a layer image."""
+    from paper_2410_00428_amd.serving import MixedIteration
+    from tests.test_gpu_serving import same_tokens
+    w = wl.workload(5)
+    sh, bs = w.shape, w.shape.block_size
+    L = sh.num_layers
+    dlens, plens, host = list(w.decode_lens[:8]), list(w.prompt_lens), list(w.offload_layers)
+    B, Td, T = len(dlens), sum(dlens), sum(plens)
+    dblk = sum(wl.blocks_for(n, bs) for n in dlens)
+    pblk = sum(wl.blocks_for(n, bs) for n in plens)
+    nblk = (L - len(host) + 3) * dblk + L * pblk + 64
+    it = MixedIteration(sh, dlens, plens, host, nblk, ring_layers=3, free_order=wl.free_list_order(5, nblk, index=3),
+                        tier_units=4, tier_threads=4)
+    scale = w.data_scale
+    # one pair of cached tensors for all layers, the roles alternating with the layer's parity; one set of prompts
+    A = wl.normal_tensor(wl.rng_for(5, "k", 900), (Td, sh.num_kv_heads, sh.head_dim), scale, "bf16")
+    Bt = wl.normal_tensor(wl.rng_for(5, "v", 900), (Td, sh.num_kv_heads, sh.head_dim), scale, "bf16")
+    kv_of = lambda l: (A, Bt) if l % 2 == 0 else (Bt, A)
+    Ad, Bd = H.to_dev(A), H.to_dev(Bt)
+    q_host = [wl.decode_qkv(5, l, 0, B, sh, scale, q_gain=0.25)[0] for l in range(L)]
+    q_dev = [H.to_dev(q) for q in q_host]
+    Q, K, V = wl.qkv(5, 901, T, sh, scale, q_gain=0.25)
+    Qd, Kd, Vd = H.to_dev(Q), H.to_dev(K), H.to_dev(V)
+    it.build_cached_state(lambda l: (Ad, Bd) if l % 2 == 0 else (Bd, Ad))
+    checked = (0, 3, 30)
+    assert 3 not in host and 0 in host and 30 in host
+    O_dec = H.empty_like_storage((L, B, sh.num_q_heads, sh.head_dim), "bf16")
+    shared = H.empty_like_storage(Q.shape, "bf16")
+    O_pf = [H.empty_like_storage(Q.shape, "bf16") if l in checked else shared for l in range(L)]
+    it.run(q_dev, O_dec, lambda l: (Qd, Kd, Vd), O_pf)
+    it.finish()
+    got = H.to_host(O_dec, "bf16")
+    starts = np.concatenate([[0], np.cumsum(dlens)])
+    for l in checked:
+        for s in (int(np.argmin(dlens)), int(np.argmax(dlens))):
+            n = dlens[s]
+            o = orc.LayerKVOracle(1, sh.num_q_heads, sh.num_kv_heads, sh.head_dim, bs, wl.blocks_for(n, bs), "bf16")
+            o.alloc_layer_blocks(0, 0, n)
+            k_l, v_l = kv_of(l)
+            o.write_kv(k_l[starts[s]:starts[s] + n], v_l[starts[s]:starts[s] + n], o.slot_mapping(0, 0, 0, n))
+            ref = o.paged_decode_attention(q_host[l][s:s + 1], o.padded_block_table([0], 0), [n], threads=THREADS)
+            H.check_attention(got[l][s:s + 1], ref, "bf16", scale, f"decode layer {l} sequence {s} ({n} tokens)")
+            if l == 30:   # the sequence's stretch of the layer's host image holds the same tokens
+                first = sum(wl.blocks_for(m, bs) for m in dlens[:s]) * sh.block_bytes
+                mine = it.images[l][first:first + wl.blocks_for(n, bs) * sh.block_bytes].tobytes()
+                assert same_tokens(mine, o.pack_layer_blocks(o.block_table(0, 0)).tobytes(), [n], sh), "layer image"
+        sampled_prefill_check(5, l, Q, K, V, O_pf[l], plens, sh, scale, [(0, 0), (0, 13), (1, 31), (1, 20)])
+    o = orc.LayerKVOracle(1, sh.num_q_heads, sh.num_kv_heads, sh.head_dim, bs, pblk, "bf16")
+    for i, n in enumerate(plens):
+        o.alloc_layer_blocks(i, 0, n)
+    o.write_kv(K, V, np.concatenate([o.slot_mapping(i, 0, 0, n) for i, n in enumerate(plens)]))
+    want = o.pack_layer_blocks(sum((o.block_table(i, 0) for i in range(len(plens))), []))
+    assert it.prompt_images[0].tobytes() == want.tobytes(), "offload image of the new prompts, layer 0"
+    it.close()
