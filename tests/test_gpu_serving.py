@@ -22,8 +22,9 @@ def same_tokens(a, b, lens, sh) -> bool:
     The slots behind a sequence's last token are not compared: a block that held another layer before keeps that
     layer's bytes there, and nothing ever reads them."""
     shape5 = (-1, sh.num_kv_heads, 2, sh.block_size, sh.head_dim)
-    a = np.frombuffer(a, dtype=np.uint16).reshape(shape5)
-    b = np.frombuffer(b, dtype=np.uint16).reshape(shape5)
+    elem = np.uint8 if sh.dtype == "fp8" else np.uint16
+    a = np.frombuffer(a, dtype=elem).reshape(shape5)
+    b = np.frombuffer(b, dtype=elem).reshape(shape5)
     if a.shape != b.shape:
         return False
     off = 0
@@ -37,9 +38,12 @@ def same_tokens(a, b, lens, sh) -> bool:
     return off == a.shape[0]
 
 
-@pytest.mark.parametrize("ring,unit_blocks,units,threads", [(2, 8, 3, 2), (1, 1, 1, 1), (3, 64, 8, 4)])
-def test_mixed_iteration_host_layers_through_a_ring_of_blocks_and_the_pageable_tier(ring, unit_blocks, units, threads):
-    sh = wl.KVShape(6, 8, 4, 128, 16, "bf16")
+@pytest.mark.parametrize("ring,unit_blocks,units,threads,dtype", [(2, 8, 3, 2, "bf16"), (1, 1, 1, 1, "bf16"),
+                                                                  (3, 64, 8, 4, "bf16"), (2, 8, 3, 2, "fp8")])
+def test_mixed_iteration_host_layers_through_a_ring_of_blocks_and_the_pageable_tier(ring, unit_blocks, units, threads,
+                                                                                    dtype):
+    sh = wl.KVShape(6, 8, 4, 128, 16, dtype)
+    scales = dict(k_scale=1 / 32, v_scale=1 / 64) if dtype == "fp8" else {}
     L, bs = sh.num_layers, sh.block_size
     dlens = [37, 500, 1200, 64, 333, 1999, 16]
     plens = [300, 170]
@@ -53,9 +57,9 @@ def test_mixed_iteration_host_layers_through_a_ring_of_blocks_and_the_pageable_t
     order = wl.free_list_order(5, nblk, index=9)
     pool = H.zero_pool(sh, nblk)
     it = MixedIteration(sh, dlens, plens, host, nblk, ring_layers=ring, free_order=order, pool=pool,
-                        tier_unit_bytes=unit_blocks * sh.block_bytes, tier_units=units, tier_threads=threads)
+                        tier_unit_bytes=unit_blocks * sh.block_bytes, tier_units=units, tier_threads=threads, **scales)
     c = it.ctx
-    o = orc.LayerKVOracle(L, sh.num_q_heads, sh.num_kv_heads, sh.head_dim, bs, L * (dblk + pblk), "bf16")
+    o = orc.LayerKVOracle(L, sh.num_q_heads, sh.num_kv_heads, sh.head_dim, bs, L * (dblk + pblk), dtype, **scales)
     scale = 0.5
     kv, qd, pq = {}, [], {}
     for l in range(L):
