@@ -564,6 +564,41 @@ def test_pageable_offload_and_reload_through_a_small_pinned_ring(unit_blocks, un
     c.destroy()
 
 
+def test_pinned_ring_reshaped_between_transfers_and_mixed_with_the_pinned_calls():
+    """lkv_host_tier_config may be called any time: the ring is rebuilt (other unit size, other unit count) between
+    an offload and its reload, and pinned pack / unpack calls, which use the same device staging with another piece
+    size, run in between; every image and the pool keep the oracle's bytes."""
+    shape = wl.KVShape(2, 4, 4, 64, 16, "bf16")
+    nblk = 96
+    c, o, pool, rng = _random_pool(shape, nblk, 35, staging_bytes=8 * shape.block_bytes)
+    side = torch.cuda.Stream()
+    ids = rng.permutation(nblk)[:37].astype(np.int32)
+    ref = o.pack_layer_blocks(ids)
+    image = np.zeros(ref.nbytes, np.uint8)
+    pinned = H.pinned_bytes(ref.nbytes)
+    for rnd, (unit_blocks, units, threads) in enumerate([(4, 2, 2), (1, 3, 1), (3, 1, 2), (4, 4, 4)]):
+        c.host_tier_config(unit_blocks * shape.block_bytes, units, threads)
+        image[:] = 0
+        c.offload_layer_pageable(0, ids, image, side)
+        c.pack_layer_blocks(1, ids, pinned, side)                 # same staging, whole-staging pieces
+        c.host_tier_synchronize(0)
+        c.event_synchronize(1, lkv.LKV_EV_OFFLOADED)
+        assert image.tobytes() == ref.tobytes(), f"round {rnd}: pageable image"
+        assert pinned.numpy()[:ref.nbytes].tobytes() == ref.tobytes(), f"round {rnd}: pinned image"
+        new_ids = rng.permutation(nblk)[:37].astype(np.int32)
+        if rnd % 2:
+            c.host_tier_config((unit_blocks + 1) * shape.block_bytes, units + 1, threads)   # reshaped before the reload
+        c.unpack_layer_blocks(1, new_ids, pinned, side)
+        o.unpack_layer_blocks(new_ids, ref.copy())
+        c.reload_layer_pageable(0, new_ids[::-1].copy(), image, side)
+        o.unpack_layer_blocks(new_ids[::-1], ref.copy())
+        c.event_synchronize(0, lkv.LKV_EV_RELOADED)
+        c.event_synchronize(1, lkv.LKV_EV_RELOADED)
+        assert H.pool_as_oracle_view(pool, o).tobytes() == o.pool.tobytes(), f"round {rnd}: pool after the reloads"
+        ref = o.pack_layer_blocks(ids)                            # the pool has changed: the next round's images
+    c.destroy()
+
+
 def test_pageable_offload_of_many_layers_back_to_back_and_repeated_layer():
     """Several layers queued behind each other on the transfer stream with fewer ring units than units in
     flight; waiting for one layer's event completes that layer's image; a second offload of a layer into the
