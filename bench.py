@@ -500,9 +500,10 @@ def main():
     decode_ctx = [[n + st + 1 for n in w.prompt_lens] for st in range(w.decode_steps)]
     decode_bytes_per_launch = [sum(c) * sh.token_bytes for c in decode_ctx]
     decode_bytes_total = sum(decode_bytes_per_launch) * L * K
-    # Kernel time = the library's own HIP events, recorded on the launch stream right before and right after
-    # each launch (lkv_set_profiling).  Events recorded from Python around the C call (eng.timers) also
-    # contain the time the GPU waits for the interpreter between two launches; they are kept for comparison.
+    # Kernel time = the library's own HIP events, attached to the kernels of each launch (lkv_set_profiling: the
+    # start event takes the kernel's begin, the stop event its end, as a profiler reports it).  Events recorded
+    # from Python around the C call (eng.timers) also contain the stream's hand-over before and after a launch and
+    # the time the GPU waits for the interpreter between two launches; they are kept for comparison.
     decode_ms_lib = stats["decode_kernel_ns"] * 1e-6
     assert stats["decode_kernel_launches"] == L * K * w.decode_steps
     decode_gbs = decode_bytes_total / (decode_ms_lib * 1e-3) / 1e9
@@ -719,8 +720,8 @@ def main():
                                f"d={sh.head_dim}, block 16, {B} prompts x {w.prompt_lens[0]} tokens, "
                                f"{len(off_layers)} layers offloaded+reloaded, {w.decode_steps} decode step(s))",
                    "value_is": "decode paged attention: context KV bytes (K and V once per kv head) / HIP-event time "
-                               "of the decode launches (events recorded by the library on the launch stream around "
-                               "each launch), measured inside the full step"},
+                               "of the decode launches (events attached by the library to each launch's kernels: begin "
+                               "of the first, end of the last), measured inside the full step"},
         "components": {
             "decode_paged_attn_GBps": round(decode_gbs, 2),
             "decode_frac_of_hbm_peak": round(decode_gbs / HBM_PEAK_GBS, 4),

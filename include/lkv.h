@@ -340,8 +340,9 @@ lkv_status lkv_stream_wait_event(lkv_ctx *ctx, int32_t layer, int32_t ev, void *
 /* Blocks the host until that event has happened (for LKV_EV_OFFLOADED of a pageable offload: until the image
  * is complete in the caller's buffer). */
 lkv_status lkv_event_synchronize(lkv_ctx *ctx, int32_t layer, int32_t ev);
-/* Turns per-launch HIP-event timing of the library's kernels on or off (off by default; each timed launch
- * costs two extra event records).  Results accumulate in lkv_stats. */
+/* Turns per-launch HIP-event timing of the library's kernels on or off (off by default).  The events are
+ * attached to the kernels themselves (the begin of a launch's first kernel, the end of its last), so the times
+ * are the kernels' own.  Results accumulate in lkv_stats. */
 lkv_status lkv_set_profiling(lkv_ctx *ctx, int32_t on);
 /* Copies min(size, sizeof(lkv_stats)) bytes of counters to out (host).  With profiling on this waits
  * for the timed launches recorded so far. */

@@ -200,7 +200,7 @@ hipError_t launch_write_kv(const lkv_ctx *c, const void *K, const void *V, const
     const int64_t ppr = c->in_row_bytes / 16;
     const int64_t total8 = num_tokens * 2 * c->cfg.num_kv_heads * ppr;
     if (total8 == 0) return hipSuccess;
-    hipLaunchKernelGGL(write_kv_e4m3_kernel<kUnrollScatter>, dim3(grid_for(total8, kUnrollScatter)), dim3(kThreads), 0, s,
+    launch_timed(c, true, true, write_kv_e4m3_kernel<kUnrollScatter>, dim3(grid_for(total8, kUnrollScatter)), dim3(kThreads), s,
                        (const char *)K, (const char *)V, slots, c->pool, total8, make_div(ppr),
                        make_div(c->cfg.num_kv_heads), make_div(c->cfg.block_size), c->in_row_bytes, c->row_bytes,
                        c->block_bytes, c->cfg.num_pool_blocks * c->cfg.block_size, 1.0f / c->k_scale, 1.0f / c->v_scale);
@@ -209,7 +209,7 @@ hipError_t launch_write_kv(const lkv_ctx *c, const void *K, const void *V, const
   int64_t pieces_per_row = c->row_bytes / 16;
   int64_t total = num_tokens * 2 * c->cfg.num_kv_heads * pieces_per_row;
   if (total == 0) return hipSuccess;
-  hipLaunchKernelGGL(write_kv_kernel<kUnrollScatter>, dim3(grid_for(total, kUnrollScatter)), dim3(kThreads), 0, s, (const char *)K, (const char *)V,
+  launch_timed(c, true, true, write_kv_kernel<kUnrollScatter>, dim3(grid_for(total, kUnrollScatter)), dim3(kThreads), s, (const char *)K, (const char *)V,
                      slots, c->pool, total, make_div(pieces_per_row), make_div(c->cfg.num_kv_heads),
                      make_div(c->cfg.block_size), c->row_bytes, c->block_bytes,
                      c->cfg.num_pool_blocks * c->cfg.block_size);
@@ -219,7 +219,7 @@ hipError_t launch_write_kv(const lkv_ctx *c, const void *K, const void *V, const
 hipError_t launch_gather_blocks(const lkv_ctx *c, const int32_t *ids_dev, int64_t n, char *dst, hipStream_t s) {
   int64_t total = n * (c->block_bytes / 16);
   if (total == 0) return hipSuccess;
-  hipLaunchKernelGGL((move_blocks_kernel<true, kUnroll>), dim3(grid_for(total, kUnroll)), dim3(kThreads), 0, s, c->pool, dst, ids_dev,
+  launch_timed(c, true, true, move_blocks_kernel<true, kUnroll>, dim3(grid_for(total, kUnroll)), dim3(kThreads), s, c->pool, dst, ids_dev,
                      total, make_div(c->block_bytes / 16), c->block_bytes);
   return hipGetLastError();
 }
@@ -227,7 +227,7 @@ hipError_t launch_gather_blocks(const lkv_ctx *c, const int32_t *ids_dev, int64_
 hipError_t launch_scatter_blocks(const lkv_ctx *c, const int32_t *ids_dev, int64_t n, const char *src, hipStream_t s) {
   int64_t total = n * (c->block_bytes / 16);
   if (total == 0) return hipSuccess;
-  hipLaunchKernelGGL((move_blocks_kernel<false, kUnrollScatter>), dim3(grid_for(total, kUnrollScatter)), dim3(kThreads), 0, s, c->pool,
+  launch_timed(c, true, true, move_blocks_kernel<false, kUnrollScatter>, dim3(grid_for(total, kUnrollScatter)), dim3(kThreads), s, c->pool,
                      const_cast<char *>(src), ids_dev, total, make_div(c->block_bytes / 16), c->block_bytes);
   return hipGetLastError();
 }

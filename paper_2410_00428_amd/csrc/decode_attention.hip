@@ -700,8 +700,8 @@ Plan make_plan(const lkv_ctx *c, int num_seqs, int max_blocks) {
 template <typename T, int D, int G, int WAVES>
 hipError_t launch_w(const lkv_ctx *c, const Plan &p, const void *Q, void *O, const int32_t *bt, int max_blocks,
                     const int32_t *cl, int num_seqs, Workspace ws, hipStream_t s) {
-  hipLaunchKernelGGL((paged_decode_kernel<T, D, G, WAVES>), dim3(c->cfg.num_kv_heads, num_seqs, p.num_parts),
-                     dim3(WAVES * 64), 0, s, (const T *)Q, (T *)O, c->pool, bt, max_blocks, cl, c->cfg.num_q_heads,
+  launch_timed(c, true, p.num_parts == 1, paged_decode_kernel<T, D, G, WAVES>, dim3(c->cfg.num_kv_heads, num_seqs, p.num_parts),
+                     dim3(WAVES * 64), s, (const T *)Q, (T *)O, c->pool, bt, max_blocks, cl, c->cfg.num_q_heads,
                      c->cfg.num_q_heads / c->cfg.num_kv_heads, c->block_bytes, (int)c->cfg.num_pool_blocks, c->scale, p.partition, p.num_parts, ws);
   return hipGetLastError();
 }
@@ -713,7 +713,7 @@ hipError_t launch_mfma(const lkv_ctx *c, const Plan &p, const void *Q, void *O, 
   if ((int64_t)c->cfg.num_kv_heads * num_seqs * p.num_parts > INT32_MAX) return hipErrorInvalidValue;
   dim3 grid((unsigned)(c->cfg.num_kv_heads * num_seqs * p.num_parts)), block(WAVES * 64);
   const int lpt = p.lpt ? 1 : 0;
-  hipLaunchKernelGGL((paged_decode_mfma_kernel<G, WAVES, FP8>), grid, block, 0, s, (const uint16_t *)Q,
+  launch_timed(c, true, p.num_parts == 1, paged_decode_mfma_kernel<G, WAVES, FP8>, grid, block, s, (const uint16_t *)Q,
                      (uint16_t *)O, c->pool, bt, max_blocks, cl, c->cfg.num_q_heads,
                      c->cfg.num_q_heads / c->cfg.num_kv_heads, c->block_bytes, (int)c->cfg.num_pool_blocks, FP8 ? c->scale * c->k_scale : c->scale, FP8 ? c->v_scale : 1.f,
                      p.partition, p.num_parts, num_seqs, lpt, ws);
@@ -744,7 +744,7 @@ hipError_t launch_t(const lkv_ctx *c, const void *Q, void *O, const int32_t *bt,
     return hipErrorInvalidValue;  // more than 8 heads per kv head only on the matrix-core kernel
   }
   if (e != hipSuccess || p.num_parts == 1) return e;
-  hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(num_seqs * Hq), dim3(D), 0, s, (T *)O, cl, max_blocks * kBlock, Hq,
+  launch_timed(c, false, true, decode_combine_kernel<T, D>, dim3(num_seqs * Hq), dim3(D), s, (T *)O, cl, max_blocks * kBlock, Hq,
                      p.partition,
                      p.num_parts, fp8 ? c->v_scale : 1.f, ws);
   return hipGetLastError();

@@ -248,33 +248,37 @@ lkv_status fold_timed(lkv_ctx *c, bool wait) {
   return LKV_OK;
 }
 
-// Kernel profiling: brackets one launch with timing events taken from a small free list.  A transfer of many
+// Kernel profiling: a region (one launch, or a launch and the merge kernel behind it) gets a pair of timing events
+// from a small free list; the launchers attach them to the region's kernels (launch_timed).  A transfer of many
 // units profiles thousands of launches between two reads of the statistics: finished pairs are folded on the
 // way, whenever kTimedBacklog more have been added, so that the number of live events stays bounded.
 constexpr size_t kTimedBacklog = 512;
-lkv_status timed_begin(lkv_ctx *c, hipStream_t s, hipEvent_t *a) {
+lkv_status timed_begin(lkv_ctx *c, hipStream_t, hipEvent_t *a) {
   *a = nullptr;
   if (!c->profiling) return LKV_OK;
-  if (c->spare_events.empty()) {
-    LKV_HIP(c, hipEventCreate(a));
-  } else {
-    *a = c->spare_events.back();
-    c->spare_events.pop_back();
+  for (hipEvent_t *e : {&c->prof_start, &c->prof_stop}) {
+    if (c->spare_events.empty()) {
+      LKV_HIP(c, hipEventCreate(e));
+    } else {
+      *e = c->spare_events.back();
+      c->spare_events.pop_back();
+    }
   }
-  LKV_HIP(c, hipEventRecord(*a, s));
+  c->prof_start_used = c->prof_stop_used = false;
+  *a = c->prof_start;
   return LKV_OK;
 }
 
-lkv_status timed_end(lkv_ctx *c, hipStream_t s, hipEvent_t a, int64_t bytes, int kind) {
+lkv_status timed_end(lkv_ctx *c, hipStream_t, hipEvent_t a, int64_t bytes, int kind) {
   if (!a) return LKV_OK;
-  hipEvent_t b;
-  if (c->spare_events.empty()) {
-    LKV_HIP(c, hipEventCreate(&b));
-  } else {
-    b = c->spare_events.back();
-    c->spare_events.pop_back();
+  hipEvent_t b = c->prof_stop;
+  const bool launched = c->prof_start_used && c->prof_stop_used;
+  c->prof_start = c->prof_stop = nullptr;
+  if (!launched) {  // the region launched nothing (or failed half way): no time to read
+    c->spare_events.push_back(a);
+    c->spare_events.push_back(b);
+    return LKV_OK;
   }
-  LKV_HIP(c, hipEventRecord(b, s));
   c->timed.push_back({a, b, bytes, kind});
   if (c->timed.size() >= c->timed_fold_at) {
     if (lkv_status st = fold_timed(c, false)) return st;

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cstdint>
 #include <string>
@@ -93,6 +94,10 @@ struct lkv_ctx {
     int64_t bytes;
     int kind;
   };
+  // the profiled region that is being launched right now: its start event goes to the first kernel of the region,
+  // its stop event to the last one (launch_timed below); null while profiling is off
+  mutable hipEvent_t prof_start = nullptr, prof_stop = nullptr;
+  mutable bool prof_start_used = false, prof_stop_used = false;
   // pageable host tier: pinned ring, one event per ring unit, the CPU threads
   lkv::HostTier tier;
   char *ring = nullptr;
@@ -109,6 +114,18 @@ struct lkv_ctx {
   std::vector<hipEvent_t> spare_events;
   mutable std::string err;
 };
+
+// Launches a kernel of the hot path.  While profiling is on, the region's timing events are attached to the
+// kernels themselves (start of the region's first kernel, end of its last): the time read from them is the kernels'
+// own, as a profiler reports it, without the stream's hand-over before and after a launch.
+template <typename Kernel, typename... Args>
+inline void launch_timed(const lkv_ctx *c, bool first, bool last, Kernel kernel, dim3 grid, dim3 block, hipStream_t s,
+                         Args... args) {
+  hipEvent_t a = first ? c->prof_start : nullptr, b = last ? c->prof_stop : nullptr;
+  hipExtLaunchKernelGGL(kernel, grid, block, 0, s, a, b, 0, args...);
+  if (a) c->prof_start_used = true;
+  if (b) c->prof_stop_used = true;
+}
 
 namespace lkv {
 

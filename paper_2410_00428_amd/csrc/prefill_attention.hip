@@ -759,10 +759,10 @@ hipError_t launch_bf16_d128(const lkv_ctx *c, const void *Q, const void *K, cons
   const float sl2 = c->scale * kLog2e;
   dim3 grid((unsigned)grid_wgs);
   if (causal)
-    hipLaunchKernelGGL((prefill_bf16_d128_kernel<true>), grid, dim3(kThreads), 0, s, (const uint16_t *)Q,
+    launch_timed(c, true, true, prefill_bf16_d128_kernel<true>, grid, dim3(kThreads), s, (const uint16_t *)Q,
                        (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, cu, Hq, Hkv, num_seqs, xcd_heads, sl2);
   else
-    hipLaunchKernelGGL((prefill_bf16_d128_kernel<false>), grid, dim3(kThreads), 0, s, (const uint16_t *)Q,
+    launch_timed(c, true, true, prefill_bf16_d128_kernel<false>, grid, dim3(kThreads), s, (const uint16_t *)Q,
                        (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, cu, Hq, Hkv, num_seqs, xcd_heads, sl2);
   return hipGetLastError();
 }
@@ -779,11 +779,11 @@ hipError_t launch_bf16(const lkv_ctx *c, const void *Q, const void *K, const voi
   const float sl2 = c->scale * kLog2e;
   dim3 grid((unsigned)total);
   if (causal)
-    hipLaunchKernelGGL((prefill_bf16_kernel<D, true, QB>), grid, dim3(kThreads), 0, s, (const uint16_t *)Q,
+    launch_timed(c, true, true, prefill_bf16_kernel<D, true, QB>, grid, dim3(kThreads), s, (const uint16_t *)Q,
                        (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, cu, c->cfg.num_q_heads,
                        c->cfg.num_kv_heads, tiles, (int)total, sl2);
   else
-    hipLaunchKernelGGL((prefill_bf16_kernel<D, false, QB>), grid, dim3(kThreads), 0, s, (const uint16_t *)Q,
+    launch_timed(c, true, true, prefill_bf16_kernel<D, false, QB>, grid, dim3(kThreads), s, (const uint16_t *)Q,
                        (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, cu, c->cfg.num_q_heads,
                        c->cfg.num_kv_heads, tiles, (int)total, sl2);
   return hipGetLastError();
@@ -794,10 +794,10 @@ hipError_t launch_f32(const lkv_ctx *c, const void *Q, const void *K, const void
                       int num_seqs, int max_seqlen, int causal, hipStream_t s) {
   dim3 grid((unsigned)((max_seqlen + 63) / 64), (unsigned)c->cfg.num_q_heads, (unsigned)num_seqs);
   if (causal)
-    hipLaunchKernelGGL((prefill_f32_kernel<D, true>), grid, dim3(kThreads), 0, s, (const float *)Q, (const float *)K,
+    launch_timed(c, true, true, prefill_f32_kernel<D, true>, grid, dim3(kThreads), s, (const float *)Q, (const float *)K,
                        (const float *)V, (float *)O, cu, c->cfg.num_q_heads, c->cfg.num_kv_heads, c->scale);
   else
-    hipLaunchKernelGGL((prefill_f32_kernel<D, false>), grid, dim3(kThreads), 0, s, (const float *)Q, (const float *)K,
+    launch_timed(c, true, true, prefill_f32_kernel<D, false>, grid, dim3(kThreads), s, (const float *)Q, (const float *)K,
                        (const float *)V, (float *)O, cu, c->cfg.num_q_heads, c->cfg.num_kv_heads, c->scale);
   return hipGetLastError();
 }
