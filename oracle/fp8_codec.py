@@ -3,8 +3,13 @@
 The paper names KV-cache quantisation as the next step of the method (its Future Work section) without fixing a
 format.  This build takes the OCP 8-bit floating point format E4M3 ("e4m3fn": 1 sign, 4 exponent, 3 mantissa
 bits, bias 7, no infinities, the all-ones pattern S.1111.111 is NaN, largest finite value 448) with one scale per
-tensor kind:  code = round_to_nearest_even(x / scale), saturated to +-448;  value = decode(code) * scale.
-Everything here is written out from that definition with Python integers and exact rationals; only ``tests/`` may
+tensor kind.  The paper leaves the quantisation step open as well; the reading taken (and documented as the
+storage contract in the library's public header) is
+    code = nearest E4M3 value, ties to even, saturated to +-448, of  y = fl32(x * fl32(1 / scale)),
+i.e. the scale is applied as ONE float32 reciprocal and ONE float32 product, each rounded once, and value =
+decode(code) * scale.  The other natural reading, the exactly divided x / scale, differs from it only where x / scale
+falls on (or within a float32 rounding of) the midpoint of two codes; ``quantize_bf16_bits_exact_division`` implements
+that reading so that a test can show where the two part and that the choice is a choice.  Everything here is written out from that definition with Python integers and exact rationals; only ``tests/`` may
 import it.  **parity unpinned** against the paper (it gives no format); pinned against the format's published
 constants, its own inverse, exact midpoints and an independent library conversion in ``tests/test_fp8.py``.
 """
@@ -76,10 +81,25 @@ def encode(x: np.ndarray) -> np.ndarray:
 
 
 def quantize_bf16_bits(bits: np.ndarray, scale: float) -> np.ndarray:
-    """bf16 bit patterns -> codes of x * inv with inv = float32(1) / float32(scale), the product taken in float32
-    (one rounding), which is what the library does on the device."""
+    """The storage contract: bf16 bit patterns -> codes of y = fl32(x * inv) with inv = fl32(1 / fl32(scale)), both
+    roundings to float32 nearest-even; the code is then decided exactly (``encode``)."""
     x = (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
     inv = np.float32(1.0) / np.float32(scale)
     with np.errstate(invalid="ignore", over="ignore"):   # NaN and infinite inputs are part of the domain
         y = (x * inv).astype(np.float32)
     return encode(y)
+
+
+def quantize_bf16_bits_exact_division(bits: np.ndarray, scale: float) -> np.ndarray:
+    """The reading NOT taken: codes of the exact quotient x / fl32(scale) (rational arithmetic, no intermediate
+    rounding).  Finite inputs only; kept to show where the two readings differ."""
+    x = (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+    sc = F(float(np.float32(scale)))
+    out = np.empty(x.shape, dtype=np.uint8)
+    flat = out.reshape(-1)
+    for i, v in enumerate(x.reshape(-1)):
+        c = encode_one(F(float(v)) / sc)
+        if v == 0 and np.signbit(v):
+            c |= 0x80
+        flat[i] = c
+    return out

@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 
 from oracle import fp8_codec as fp8
+from paper_2410_00428_amd import workloads as wl
 
 torch = pytest.importorskip("torch")
 
@@ -69,6 +70,25 @@ def test_quantize_applies_one_float32_multiply():
     # a scale whose reciprocal is inexact: the product is rounded once to float32 before the code is chosen
     x = np.float32(1.0) * (np.float32(1.0) / np.float32(3.0))
     assert fp8.quantize_bf16_bits(np.array([0x3F80], np.uint16), 3.0)[0] == fp8.encode_one(F(float(x)))
+
+
+def test_reciprocal_product_and_exact_division_are_two_readings_that_differ_at_midpoints():
+    """The paper fixes no format, so the quantisation step is a reading: the contract multiplies by the float32
+    reciprocal of the scale.  1.3671875 / 7 = 0.1953125 is EXACTLY half way between the codes 0x24 (0.1875) and 0x25
+    (0.203125): exact division rounds the tie to the even code 0x24, while fl32(1/7) lies a little above 1/7 and the
+    product a little above the midpoint, which gives 0x25.  Away from such midpoints the two agree."""
+    x = np.array([0x3FAF], dtype=np.uint16)                       # 1.3671875 as bf16
+    assert F(float(wl.bf16_bits_to_f32(x)[0])) / 7 == (fp8.POSITIVE[0x24] + fp8.POSITIVE[0x25]) / 2
+    assert fp8.quantize_bf16_bits_exact_division(x, 7.0)[0] == 0x24
+    assert fp8.quantize_bf16_bits(x, 7.0)[0] == 0x25
+    # powers of two have exact reciprocals: no difference anywhere, midpoints included
+    every = np.arange(0x3C00, 0x4400, dtype=np.uint16)
+    for scale in (0.5, 4.0):
+        assert np.array_equal(fp8.quantize_bf16_bits(every, scale), fp8.quantize_bf16_bits_exact_division(every, scale))
+    # an inexact reciprocal: the readings part on a few patterns only, all of them within one code of each other
+    a, b = fp8.quantize_bf16_bits(every, 7.0), fp8.quantize_bf16_bits_exact_division(every, 7.0)
+    diff = np.flatnonzero(a != b)
+    assert 0 < len(diff) < len(every) // 20 and (np.abs(a[diff].astype(int) - b[diff].astype(int)) == 1).all()
 
 
 def test_oracle_fp8_pool_decode_equals_decode_over_the_dequantised_values():

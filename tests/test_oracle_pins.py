@@ -352,6 +352,33 @@ def test_free_seq_releases_everything():
     assert o.num_free_blocks() == 31 and o.block_table(7, 2) == []
 
 
+def test_free_seq_release_order_replays_the_stack_model():
+    """A finished request gives its layers back lowest layer first, each table in table order, onto the stack: the
+    ids handed out next are the LAST layer's table read backwards, then the layer before it, and so on.  Checked
+    against an independent list model, with another request's blocks in between."""
+    N, bs, L = 24, 4, 3
+    order = [int(v) for v in np.random.default_rng(31).permutation(N)]
+    o = orc.LayerKVOracle(L, 1, 1, 4, bs, N, "f32")
+    o.pool_reset(order)
+    stack = order[::-1]
+    tabs = {}
+    for seq, layer, tokens in ((7, 0, 9), (8, 1, 5), (7, 2, 4), (7, 1, 13), (8, 0, 1)):
+        o.alloc_layer_blocks(seq, layer, tokens)
+        tabs[(seq, layer)] = [stack.pop() for _ in range(-(-tokens // bs))]
+        assert o.block_table(seq, layer) == tabs[(seq, layer)]
+    t70, t71, t72 = tabs[(7, 0)], tabs[(7, 1)], tabs[(7, 2)]       # 3, 4 and 1 blocks
+    o.free_seq(7)
+    for layer in range(L):                      # the model: lowest layer first, each table in table order
+        stack.extend(tabs.pop((7, layer)))
+    assert o.num_free_blocks() == len(stack)
+    assert [o.layer_residency(7, l) for l in range(L)] == [None] * L
+    # the stack hands out the last layer's blocks first, each table backwards: written out, not derived
+    o.alloc_layer_blocks(9, 0, 8 * bs)
+    assert o.block_table(9, 0) == t72[::-1] + t71[::-1] + t70[::-1]
+    assert o.block_table(9, 0) == [stack.pop() for _ in range(8)]
+    assert o.block_table(8, 1) == tabs[(8, 1)] and o.block_table(8, 0) == tabs[(8, 0)]   # the other request: untouched
+
+
 def test_retained_layers_matches_the_papers_example():
     txt = dict(line.split(None, 1) for line in open(os.path.join(GOLDEN, "retained_layers_L8_x4.txt"))
                if not line.startswith("#"))
