@@ -1,16 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the layer-wise paged KV cache hot path on one MI355X.
 
-One "step" is one pass of the whole path over one batch of synthetic input of the chosen
-workload (default: workload 2, LLaMA-2-7B-shaped, 8 prompts x 2048 tokens, bf16):
-for every layer allocate + map, write K/V, causal prefill attention, and for the offloaded
-layers pack + copy to pinned host memory on a side stream; then reload those layers and run one
-decode step (append one token per sequence per layer, paged decode attention).  Inputs are
-resident in HBM before the timed region starts.  Prints ONE JSON line.
+Default: workload 5, the largest configuration that runs on one GPU (LLaMA-2-7B KV shape, bf16): one "step" is one
+mixed serving iteration at full size (see mixed_iteration below): 64 decoding sequences whose 24 host-resident
+layers are reloaded through a ring of blocks, paged decode attention of every layer, and two new 8192-token prompts
+that are written, attended (causal prefill) and offloaded in the same iteration.  The same line carries, as named
+components, a full step of workload 3 (4 prompts x 16384 tokens: write, causal prefill, 24 layers offloaded and
+reloaded, 64 decode steps) and of workload 2 (8 x 2048, 16 layers offloaded and reloaded, one decode step), each
+with its own short warm-up and step count.  Inputs are resident in HBM before a timed region starts.  Prints ONE
+JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2|3|5] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 5|3|2] [--no-components] [--no-cpu-baseline]
 
---workload 5 is a different step: one mixed serving iteration at full size (see mixed_iteration below).
+--workload 2 / 3 time that workload's step alone (allocate + map, write K/V, causal prefill attention, pack + copy
+of the offloaded layers on a side stream, reload, decode steps) with all of its extra measurements.
 """
 from __future__ import annotations
 
@@ -27,10 +30,27 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
-# HBM bytes per launch of the dominant kernel (prefill_bf16_d128_kernel) from two rocprofv3 --pmc runs of this
-# command (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for the pack gather
-# kernel, which moves a known 256 MiB each way: see profiles/bench_workload2_hbm_traffic.md
-TRAFFIC_BYTES = {2: 513.4 * 2**20 + 128.0 * 2**20}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.md")
+
+
+def measured_traffic(kernel: str, workload: int):
+    """HBM bytes per launch of `kernel` at `workload` as two rocprofv3 --pmc runs counted them (FETCH_SIZE, then
+    WRITE_SIZE, each scaled by what the same counter reads for a copy kernel of known size).  The one place these
+    figures live is the table of profiles/hbm_traffic.md (rows `| kernel | workload | fetched bytes | written bytes
+    | ...`), which also gives the commands and the scale factors; None when the table has no such row."""
+    try:
+        rows = open(TRAFFIC_FILE).read().splitlines()
+    except OSError:
+        return None
+    for line in rows:
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 4 and cells[0] == kernel and cells[1] == str(workload):
+            try:
+                return float(cells[2]) + float(cells[3])
+            except ValueError:
+                return None
+    return None
+
 METRIC = "decode paged-attn HBM GB/s; prefill attn TFLOP/s; layer offload/reload GB/s"
 
 
@@ -39,10 +59,14 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", type=int, default=2, choices=(2, 3, 5),
-                    help="2 (default, the headline configuration), 3, or 5: the mixed serving iteration with the "
-                         "decode batch's host layers in ordinary host memory (needs ~200 GiB of host memory at 64 "
-                         "decode sequences)")
+    ap.add_argument("--workload", type=int, default=5, choices=(2, 3, 5),
+                    help="5 (default, the largest single-GPU configuration): the mixed serving iteration with the "
+                         "decode batch's host layers in ordinary host memory (needs ~215 GiB of host memory at 64 "
+                         "decode sequences), with a step of workloads 3 and 2 as components; 2 or 3: that workload alone")
+    ap.add_argument("--no-components", action="store_true",
+                    help="workload 5 only: skip the steps of workloads 3 and 2 that the line carries as components")
+    ap.add_argument("--component-steps", type=int, default=0,
+                    help="timed steps of the workload 3 / workload 2 components (0: 2 resp. 5)")
     ap.add_argument("--decode-seqs", type=int, default=64, help="workload 5: decoding sequences (64 = the full size)")
     ap.add_argument("--ring-layers", type=int, default=3, help="workload 5: sets of blocks the host layers pass through")
     ap.add_argument("--tier-unit-mib", type=int, default=64, help="workload 5: size of one unit of the pinned ring")
@@ -121,9 +145,10 @@ def cpu_baseline(w, seconds: float, lens=None) -> dict:
     n0 = w.prompt_lens[0]
     Q1, K1, V1 = (wl.normal_tensor(rng, (n0, h, sh.head_dim), w.data_scale, sh.dtype)
                   for h in (sh.num_q_heads, sh.num_kv_heads, sh.num_kv_heads))
-    rows = wl.sample_rows(rng, n0, 64)
-    tok = np.repeat(rows, 2)
-    head = np.tile(np.array([0, sh.num_q_heads - 1], dtype=np.int32), len(rows))
+    # about a tenth of the layer's causal flops: every head, a seeded sample of rows (a few seconds on 16 cores)
+    rows = wl.sample_rows(rng, n0, min(n0, 1024))
+    tok = np.repeat(rows, sh.num_q_heads)
+    head = np.tile(np.arange(sh.num_q_heads, dtype=np.int32), len(rows))
     t1 = time.perf_counter()
     orc.prefill_attention_rows(Q1, K1, V1, [0, n0], sh.dtype, tok, head, threads=threads)
     t_rows = time.perf_counter() - t1
@@ -133,10 +158,11 @@ def cpu_baseline(w, seconds: float, lens=None) -> dict:
                       f"{sh.num_q_heads} heads, contexts {min(lens)}..{max(lens)}, {kv_bytes / 2**20:.0f} MiB KV), fp64 accumulators, "
                       f"{reps} repetitions in {el:.1f} s",
             "prefill_tflops": round(flops_rows / t_rows / 1e12, 6),
-            "prefill_sample": f"{len(tok)} sampled causal rows of one {n0}-token prompt", **movers}
+            "prefill_sample": f"{len(rows)} sampled causal rows x {sh.num_q_heads} heads of one {n0}-token prompt "
+                              f"({flops_rows:.3g} flop in {t_rows:.1f} s)", **movers}
 
 
-def decode_other_workloads(torch, dev) -> dict:
+def decode_other_workloads(torch, dev, numbers=(3, 4, 5)) -> dict:
     """Paged decode attention of the other configurations' decode batches (not bench lines: context for the
     headline figure).  A few layers of the workload's KV, blocks handed out in a seeded random order over the pool,
     the layers taken in turn so that nothing stays in the last-level cache; kernel time from the library's events."""
@@ -144,6 +170,8 @@ def decode_other_workloads(torch, dev) -> dict:
     from paper_2410_00428_amd import workloads as wl
     out = {}
     for number, layers in ((3, 8), (4, 16), (5, 2)):
+        if number not in numbers:
+            continue
         w = wl.workload(number)
         sh = w.shape
         lens = [n + 1 for n in w.prompt_lens] if number == 3 else list(w.decode_lens)
@@ -254,7 +282,7 @@ def pinned_copy_peak(torch, dev) -> dict:
     return link
 
 
-def mixed_iteration(args) -> None:
+def mixed_iteration(args) -> dict:
     """Workload 5 at its full size: 64 decoding sequences (contexts uniform in [128, 16384], ~8 GiB of KV per
     layer) of which 24 of 32 layers live in ORDINARY host memory (~194 GiB) and come back through a ring of
     blocks, plus two new 8192-token prompts that prefill and offload in the same iteration.  One step = one such
@@ -394,9 +422,17 @@ def mixed_iteration(args) -> None:
                      "launch_ms": round(d["decode_kernel_ns"] * 1e-6 / (L * K), 4), "bytes_per_launch": kv_bytes},
     }
     it.close()
+    del it, O_ref, O_dec, q_dec, pq, O_pf
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
+    out["roofline"]["traffic"] = measured_traffic("paged_decode_mfma_kernel", 5) if args.kv_dtype == "bf16" else None
+    if not args.no_extras:
+        # the decode batches of the other configurations (the 70B-shaped GQA batch of workload 4 among them)
+        out["decode_other_workloads"] = decode_other_workloads(torch, dev, numbers=(3, 4))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds, lens=sorted(dlens)[len(dlens) // 2 - 1:len(dlens) // 2 + 1])
-    print(json.dumps(out))
+    return out
 
 
 def main():
@@ -404,12 +440,38 @@ def main():
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
-    if args.workload == 5:
-        return mixed_iteration(args)
+    if args.workload != 5:
+        print(json.dumps(prefill_decode_workload(args, args.workload, args.steps, args.warmup, component=False)))
+        return
+    out = mixed_iteration(args)
+    if not args.no_components and args.kv_dtype == "bf16":
+        # a full step of the two prefill-heavy configurations, so that the same line carries the 16k-token prefill,
+        # the 64-step split decode and the offload / reload of whole layers
+        for number, steps, warmup in ((3, args.component_steps or 2, 1), (2, args.component_steps or 5, 2)):
+            print(f"[bench] component: workload {number}, {warmup} warm-up + {steps} timed steps", file=sys.stderr, flush=True)
+            full = prefill_decode_workload(args, number, steps, warmup, component=True)
+            out[f"workload{number}"] = {k: full[k] for k in ("config", "steps", "warmup", "ms_per_step", "components",
+                                                            "overlap", "kernels_alone", "roofline", "rooflines_other")}
+    print(json.dumps(out))
+
+
+def prefill_decode_workload(args, number: int, steps: int, warmup: int, component: bool) -> dict:
+    """One step = S0-S6 over the workload's batch: per layer allocate + map, write, causal prefill attention, offload of
+    the workload's host layers on a side stream; then their reload and the workload's decode steps.  component: the
+    figures the default line carries for workloads 3 and 2 (no CPU baseline, no other-workload extras)."""
+    import gc
     import torch
     from paper_2410_00428_amd import workloads as wl
     from paper_2410_00428_amd.engine import LayerKVEngine
 
+    class _A:   # this run's view of the arguments
+        pass
+    run = _A()
+    run.__dict__.update(vars(args))
+    run.workload, run.steps, run.warmup = number, steps, warmup
+    if component:
+        run.no_cpu_baseline, run.no_extras = True, True
+    args = run
     w = wl.workload(args.workload)
     sh = w.shape
     L, B = sh.num_layers, len(w.prompt_lens)
@@ -475,20 +537,9 @@ def main():
     eng.ctx.set_profiling(False)
     eng.timing = True
     eng.timers.clear()
-    # in this extra step a one-wavefront kernel behind every layer's attention launch reads the shader clock (two
-    # samples ~20 us apart), to show what the power management makes of the prefill burst
-    clk_buf = torch.zeros(L, 4, dtype=torch.int64, device=dev)
-    clk_khz = []
-    step(lambda l: clk_khz.append(eng.ctx.probe_clock_trace(clk_buf[l], 2, 40000, eng.main)))
+    step()
     ms = eng.elapsed_ms()
     eng.timing = False
-    clk = clk_buf.cpu().numpy()
-    clk_mhz = (clk[:, 3] - clk[:, 1]) / np.maximum(clk[:, 2] - clk[:, 0], 1) * (clk_khz[0] / 1000.0)
-    clock_trace = {"after_layer_MHz": [round(float(x)) for x in clk_mhz],
-                   "min_MHz": round(float(clk_mhz.min())), "median_MHz": round(float(np.median(clk_mhz))),
-                   "prefill_us_per_layer": [round(x * 1e3) for x in ms.get("prefill_attention", [])],
-                   "note": "lkv_probe_clock_trace behind every layer's attention launch of one extra step: shader "
-                           "cycles per tick of the constant-rate clock over ~20 us"}
 
     K = args.steps
     def total(name):
@@ -586,10 +637,10 @@ def main():
         iso["offload_GBps"] = layer_bytes * len(off_layers) / (t_link * 1e-3) / 1e9
         iso["reload_GBps"] = layer_bytes * len(off_layers) / (t_reload * 1e-3) / 1e9
         # the same layers through the pageable tier: ordinary host memory behind the library's small pinned ring
-        pageable = np.ones(layer_bytes * len(off_layers), dtype=np.uint8)   # touched before timing
+        pageable = np.ones(layer_bytes * len(off_layers) if not component else 0, dtype=np.uint8)   # touched before timing
         views = {l: pageable[i * layer_bytes:(i + 1) * layer_bytes] for i, l in enumerate(off_layers)}
         t_page = {}
-        for rep in range(2):                                                # first pass builds the ring
+        for rep in range(0 if component else 2):                            # first pass builds the ring
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             for l in off_layers:
@@ -610,15 +661,16 @@ def main():
         s3 = eng.ctx.get_stats()
         for l in off_layers:
             eng.host_images[l] = pinned[l]
-        iso["pageable_tier"] = {
-            "offload_GBps": round(layer_bytes * len(off_layers) / t_page["offload"] / 1e9, 2),
-            "reload_GBps": round(layer_bytes * len(off_layers) / t_page["reload"] / 1e9, 2),
-            "pinned_ring_MiB": 128, "host_image_MiB": pageable.nbytes >> 20,
-            "memcpy_GBps_per_thread": round(s3["tier_copy_bytes"] / max(s3["tier_copy_ns"], 1), 1),
-            "image_ends_equal_pinned_path": bool(same),
-            "note": "lkv_offload_layer_pageable / lkv_reload_layer_pageable: wall time until the image is complete "
-                    "in ordinary host memory (4 CPU threads drain 4 pinned units of 32 MiB), resp. until the blocks "
-                    "are back in the pool"}
+        if not component:
+          iso["pageable_tier"] = {
+              "offload_GBps": round(layer_bytes * len(off_layers) / t_page["offload"] / 1e9, 2),
+              "reload_GBps": round(layer_bytes * len(off_layers) / t_page["reload"] / 1e9, 2),
+              "pinned_ring_MiB": 128, "host_image_MiB": pageable.nbytes >> 20,
+              "memcpy_GBps_per_thread": round(s3["tier_copy_bytes"] / max(s3["tier_copy_ns"], 1), 1),
+              "image_ends_equal_pinned_path": bool(same),
+              "note": "lkv_offload_layer_pageable / lkv_reload_layer_pageable: wall time until the image is complete "
+                      "in ordinary host memory (4 CPU threads drain 4 pinned units of 32 MiB), resp. until the blocks "
+                      "are back in the pool"}
         del pageable, views
         _, t_both = prefill_phase(True)
         # only the compute issued after the first offload can hide anything
@@ -627,6 +679,7 @@ def main():
                    "both_ms": round(t_both, 3),
                    "hidden_frac": round(max(0.0, 1 - (t_both - t_compute) / t_link), 4),
                    "bound": round(min(1.0, t_hideable / t_link), 4),
+                   "hidden_over_bound": round(max(0.0, 1 - (t_both - t_compute) / t_link) / max(min(1.0, t_hideable / t_link), 1e-9), 4),
                    "note": "hidden = 1 - (wall(prefill with offload) - wall(prefill alone)) / wall(offload alone); bound = "
                            "compute issued after the first offload starts / link time: attention-only compute cannot "
                            "hide a PCIe transfer of the same layers"}
@@ -703,12 +756,8 @@ def main():
     iso["prefill_attn_TFLOPs"] = pf_flops / (t_prefill * 1e-3) / 1e12
     iso["decode_paged_attn_GBps"] = decode_bytes_per_launch[0] / (t_decode * 1e-3) / 1e9
     iso = {k: (round(v, 2) if isinstance(v, float) else v) for k, v in iso.items()}
-    traffic = TRAFFIC_BYTES.get(args.workload) if args.kv_dtype == "bf16" else None
-    # what a pure bf16 MFMA stream sustains on this machine right now (random operand bits, as in real data; then
-    # constant operands): the published peak assumes the boost clock, which a matrix load does not hold
+    traffic = measured_traffic("prefill_bf16_d128_kernel", args.workload) if args.kv_dtype == "bf16" else None
     torch.cuda.synchronize()
-    mf_rand = c.probe_mfma_rate(30.0, True, eng.main)
-    mf_const = c.probe_mfma_rate(30.0, False, eng.main)
     others = None if args.no_extras else decode_other_workloads(torch, dev)
     fp8_fig = None if args.no_extras else fp8_pool_figures(torch, dev)
 
@@ -751,16 +800,7 @@ def main():
         "roofline": {"kernel": "prefill_bf16_d128_kernel (lkv_prefill_attention)", "bound": "mfma",
                      "achieved": round(prefill_tflops, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(prefill_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic,
-                     "launch_ms": round(prefill_ms_lib, 4), "flops_per_launch": pf_flops,
-                     "mfma_stream_sustained": {
-                         "random_operands_TFLOPs": round(mf_rand[0], 1), "random_operands_clock_MHz": round(mf_rand[1]),
-                         "constant_operands_TFLOPs": round(mf_const[0], 1),
-                         "constant_operands_clock_MHz": round(mf_const[1]),
-                         "frac_of_random_operand_stream": round(prefill_tflops / mf_rand[0], 4),
-                         "note": "lkv_probe_mfma_rate: nothing but v_mfma_f32_32x32x16_bf16 for 30 ms, two wavefronts "
-                                 "per SIMD; the clock under a matrix load depends on the operand bits, so the published "
-                                 "2.5 PFLOP/s (2.4 GHz) is not reachable with real data on this box"}},
-        "shader_clock_during_step": clock_trace,
+                     "launch_ms": round(prefill_ms_lib, 4), "flops_per_launch": pf_flops},
         "rooflines_other": {
             "decode": {"bound": "hbm", "achieved": round(decode_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                        "frac": round(decode_gbs / HBM_PEAK_GBS, 4)},
@@ -775,9 +815,12 @@ def main():
         "fp8_pool": fp8_fig,
     }
     eng.close()
+    del eng, Qs, Ks, Vs, O, dq, dk, dv, dO, pinned, slots_all, slot_rows, bt_all, bt_rows
+    gc.collect()
+    torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds)
-    print(json.dumps(out))
+    return out
 
 
 if __name__ == "__main__":

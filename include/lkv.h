@@ -78,8 +78,12 @@ typedef enum {
  * attention reads.  Attention kernels: head_dim 128 only. */
 typedef enum { LKV_F32 = 0, LKV_BF16 = 1, LKV_FP8_E4M3 = 2 } lkv_dtype;
 
-/* residency of one (request, layer), Section 3.2.2 */
-enum { LKV_RES_NONE = 0, LKV_RES_GPU = 1, LKV_RES_HOST = 2 };
+/* residency of one (request, layer), Section 3.2.2: where its KV lives.  LKV_RES_IN_FLIGHT is reported instead of
+ * GPU or HOST while a transfer of that layer which this context has queued is not finished yet (a HOST layer whose
+ * device-to-host copy, CPU copies of a pageable offload included, is still running: the image is not complete; a GPU
+ * layer whose reload has been queued and has not finished: its blocks do not hold the data yet).  The transfer
+ * events are per layer, so every request's entry for that layer reads IN_FLIGHT meanwhile. */
+enum { LKV_RES_NONE = 0, LKV_RES_GPU = 1, LKV_RES_HOST = 2, LKV_RES_IN_FLIGHT = 3 };
 
 /* per-layer events the library records (Section 4: transfers run on their own stream,
  * concurrently with compute, and are ordered against it per layer) */
@@ -177,6 +181,7 @@ lkv_status lkv_free_seq(lkv_ctx *ctx, int64_t seq);
 lkv_status lkv_get_block_table(const lkv_ctx *ctx, int64_t seq, int32_t layer, int32_t *out, int64_t cap, int64_t *n);
 /* out[i] (host) = slot of token position pos0+i of (seq, layer): table[p/bs]*bs + p%bs. */
 lkv_status lkv_build_slot_mapping(const lkv_ctx *ctx, int64_t seq, int32_t layer, int64_t pos0, int64_t count, int64_t *out);
+/* *out = LKV_RES_* of (seq, layer).  Never blocks: an unfinished transfer is found by querying its event. */
 lkv_status lkv_layer_residency(const lkv_ctx *ctx, int64_t seq, int32_t layer, int32_t *out);
 int64_t lkv_num_free_blocks(const lkv_ctx *ctx);
 /* Which layers keep their KV on the GPU when x of num_layers are retained: spread evenly,
@@ -255,7 +260,10 @@ lkv_status lkv_write_kv(lkv_ctx *ctx, int32_t layer, const void *K, const void *
  * int32[num_seqs+1], sequence s is tokens cu[s]..cu[s+1].  Row i of a sequence sees keys
  * 0..i if causal != 0, all keys otherwise.  max_seqlen >= the longest sequence (sizes the
  * grid).  total_tokens = T (host-known, = cu[num_seqs]; the launch is sized from it and from max_seqlen: with
- * values smaller than the batch's, rows of O stay unwritten).  `layer` selects no data; it names
+ * values smaller than the batch's, rows of O stay unwritten).  cu_seqlens is device memory the host cannot check:
+ * the kernels cut every sequence to 0 <= cu[s] <= cu[s+1] <= total_tokens and to max_seqlen tokens, so entries
+ * that are out of order or too large give wrong or unwritten rows but never touch memory outside the four tensors'
+ * total_tokens rows.  `layer` selects no data; it names
  * the layer whose compute this is, for the statistics.  bf16: fp32 accumulation, probabilities
  * rounded to bf16 before the value product; f32: fp32 throughout. */
 lkv_status lkv_prefill_attention(lkv_ctx *ctx, int32_t layer, const void *Q, const void *K, const void *V,
@@ -326,13 +334,20 @@ lkv_status lkv_set_link_gate(lkv_ctx *ctx, lkv_link_busy_fn busy, void *user, in
  * outside the pool); context_lens: device, int32[num_seqs] (a value above 16*max_blocks_per_seq is cut there);
  * sequence s attends to positions 0..context_lens[s]-1; a zero context gives a zero row.
  * Waits (on `stream`) for LKV_EV_RELOADED of the layer.  Long contexts are split into
- * partitions whose partial results are merged by a second kernel; the split-K workspace is
- * grown with hipMalloc when a call needs more than any earlier one.  A context has ONE workspace:
- * split calls of one context must not run at the same time on different streams (calls on one stream,
- * or ordered by events, are fine). */
+ * partitions whose partial results are merged by a second kernel; the partial results go through the context's
+ * split-K workspace.  This call never allocates and never synchronises: the workspace is the one lkv_create made
+ * (32 MiB: enough for 256 sequences of 16384 tokens with 32 query heads) or the one the last
+ * lkv_reserve_decode_workspace made; a call that needs more returns LKV_ERR_INVALID_ARG and enqueues nothing.
+ * A context has ONE workspace: split calls of one context must not run at the same time on different streams
+ * (calls on one stream, or ordered by events, are fine). */
 lkv_status lkv_paged_decode_attention(lkv_ctx *ctx, int32_t layer, const void *Q, void *O,
                                       const int32_t *block_table, int32_t max_blocks_per_seq,
                                       const int32_t *context_lens, int32_t num_seqs, void *stream);
+
+/* Makes the split-K workspace large enough for lkv_paged_decode_attention calls with up to num_seqs sequences and
+ * tables of max_blocks_per_seq entries (never shrinks it).  Not a hot-path call: when the workspace has to grow it
+ * waits for the device (earlier launches may still use the old one), frees it and allocates the new one. */
+lkv_status lkv_reserve_decode_workspace(lkv_ctx *ctx, int32_t num_seqs, int32_t max_blocks_per_seq);
 
 /* ------------------------------------------------------------------ ordering and statistics */
 /* Makes `stream` wait for the last recorded event `ev` of `layer` (no-op if never recorded). */
@@ -347,22 +362,6 @@ lkv_status lkv_set_profiling(lkv_ctx *ctx, int32_t on);
 /* Copies min(size, sizeof(lkv_stats)) bytes of counters to out (host).  With profiling on this waits
  * for the timed launches recorded so far. */
 lkv_status lkv_get_stats(lkv_ctx *ctx, lkv_stats *out, int64_t size);
-
-/* Measurement helper, not a step of the path: runs a stream of bf16 MFMAs (v_mfma_f32_32x32x16_bf16, two
- * wavefronts per SIMD on every CU, nothing else in the loop) for about `millis` milliseconds (clamped to 200) on
- * the context's device and `stream`, and reports the rate it sustained (*tflops, host) and the average shader
- * clock during the run (*clock_mhz, host).  random_operands != 0 uses operands with random signs and mantissas,
- * 0 uses the constant 1.0: under a matrix load the clock, and with it the reachable rate, depends on how many
- * operand bits toggle.  Blocks the host; allocates and frees a few bytes of device memory. */
-lkv_status lkv_probe_mfma_rate(lkv_ctx *ctx, double millis, int32_t random_operands, double *tflops,
-                               double *clock_mhz, void *stream);
-/* Measurement helper: enqueues on `stream` one wavefront that writes n pairs (tick of the constant-rate clock,
- * shader cycle count) to out (device, 2*n int64), about gap_cycles shader cycles apart, and exits; returns at once.
- * *wall_clock_khz (host) = rate of the constant-rate clock.  The shader clock between two samples is
- * (cycles[i+1]-cycles[i]) / (ticks[i+1]-ticks[i]) * wall_clock_khz: put next to work on another stream it shows what
- * the power management makes of that load.  1 <= n <= 1 << 20, 0 <= gap_cycles <= 1 << 24. */
-lkv_status lkv_probe_clock_trace(lkv_ctx *ctx, int64_t *out, int32_t n, int32_t gap_cycles, int32_t *wall_clock_khz,
-                                 void *stream);
 
 #ifdef __cplusplus
 }

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(HERE, "liblkv.so")
 LKV_OK, LKV_ERR_INVALID_ARG, LKV_ERR_NO_BLOCKS, LKV_ERR_NOT_RESIDENT = 0, 1, 2, 3
 LKV_ERR_HOST_MEMORY, LKV_ERR_DEVICE, LKV_ERR_UNSUPPORTED = 4, 5, 6
 LKV_F32, LKV_BF16, LKV_FP8_E4M3 = 0, 1, 2
-LKV_RES_NONE, LKV_RES_GPU, LKV_RES_HOST = 0, 1, 2
+LKV_RES_NONE, LKV_RES_GPU, LKV_RES_HOST, LKV_RES_IN_FLIGHT = 0, 1, 2, 3
 LKV_EV_KV_WRITTEN, LKV_EV_PACKED, LKV_EV_OFFLOADED, LKV_EV_RELOADED = 0, 1, 2, 3
 STATUS_NAMES = {0: "LKV_OK", 1: "LKV_ERR_INVALID_ARG", 2: "LKV_ERR_NO_BLOCKS", 3: "LKV_ERR_NOT_RESIDENT",
                 4: "LKV_ERR_HOST_MEMORY", 5: "LKV_ERR_DEVICE", 6: "LKV_ERR_UNSUPPORTED"}
@@ -35,7 +35,7 @@ EXPORTS = (
     "lkv_host_tier_config", "lkv_offload_layer_pageable", "lkv_reload_layer_pageable", "lkv_host_tier_synchronize",
     "lkv_set_link_gate",
     "lkv_stream_wait_event", "lkv_event_synchronize", "lkv_set_profiling", "lkv_get_stats",
-    "lkv_probe_mfma_rate", "lkv_probe_clock_trace",
+    "lkv_reserve_decode_workspace",
     "lkv_prefill_time", "lkv_offload_time", "lkv_plan_offload", "lkv_allow_prefill_time", "lkv_max_prefills",
     "lkv_forecast_avail", "lkv_pressure_offload",
 )
@@ -132,8 +132,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "lkv_event_synchronize": (i32, [vp, i32, i32]),
         "lkv_set_profiling": (i32, [vp, i32]),
         "lkv_get_stats": (i32, [vp, P(LkvStats), i64]),
-        "lkv_probe_mfma_rate": (i32, [vp, ctypes.c_double, i32, P(ctypes.c_double), P(ctypes.c_double), vp]),
-        "lkv_probe_clock_trace": (i32, [vp, vp, i32, i32, P(i32), vp]),
+        "lkv_reserve_decode_workspace": (i32, [vp, i32, i32]),
         "lkv_prefill_time": (ctypes.c_double, [P(CostModel), i64]),
         "lkv_offload_time": (ctypes.c_double, [P(CostModel), i64, i32]),
         "lkv_plan_offload": (i32, [P(CostModel), i64, P(i32), vp]),
@@ -397,19 +396,8 @@ class LKV:
     def set_profiling(self, on: bool) -> None:
         self._check(self.lib.lkv_set_profiling(self.h, int(bool(on))))
 
-    def probe_mfma_rate(self, millis: float = 20.0, random_operands: bool = True, stream=None):
-        """(TFLOP/s, shader clock in MHz) a pure bf16 MFMA stream sustains on this GPU right now."""
-        tf, mhz = ctypes.c_double(0.0), ctypes.c_double(0.0)
-        self._check(self.lib.lkv_probe_mfma_rate(self.h, float(millis), int(bool(random_operands)), ctypes.byref(tf),
-                                                 ctypes.byref(mhz), _stream(stream)))
-        return tf.value, mhz.value
-
-    def probe_clock_trace(self, out, n: int, gap_cycles: int = 100000, stream=None) -> int:
-        """Enqueues the clock sampler (n pairs of tick, shader cycles into ``out``: device, 2*n int64); returns the
-        tick rate in kHz.  Marshalling only: turning the pairs into MHz is the caller's."""
-        khz = ctypes.c_int32(0)
-        self._check(self.lib.lkv_probe_clock_trace(self.h, _ptr(out), n, gap_cycles, ctypes.byref(khz), _stream(stream)))
-        return khz.value
+    def reserve_decode_workspace(self, num_seqs: int, max_blocks_per_seq: int) -> None:
+        self._check(self.lib.lkv_reserve_decode_workspace(self.h, num_seqs, max_blocks_per_seq))
 
     def get_stats(self) -> dict:
         s = LkvStats()

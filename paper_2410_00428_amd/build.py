@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblkv.so")
-SOURCES = ["lkv_host.cpp", "lkv_policy.cpp", "copy_kernels.hip", "decode_attention.hip", "prefill_attention.hip", "probe_kernels.hip"]
+SOURCES = ["lkv_host.cpp", "lkv_policy.cpp", "copy_kernels.hip", "decode_attention.hip", "prefill_attention.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
          # packed-fp32 VALU forms are kept out of all device code on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -287,6 +287,8 @@ lkv_status timed_end(lkv_ctx *c, hipStream_t, hipEvent_t a, int64_t bytes, int k
   return LKV_OK;
 }
 
+constexpr int64_t kDefaultDecodeWorkspace = (int64_t)32 << 20;
+
 }  // namespace
 
 extern "C" {
@@ -373,6 +375,15 @@ static lkv_status create_impl(const lkv_config *cfg, lkv_ctx **out, bool with_de
       return bail(LKV_ERR_DEVICE);
     }
   }
+  // the split-K workspace of decode attention: allocated here (and by lkv_reserve_decode_workspace), never by the
+  // hot call
+  e = hipMalloc((void **)&c->ws, (size_t)kDefaultDecodeWorkspace);
+  if (e != hipSuccess) {
+    c->ws = nullptr;
+    c->err = std::string("hipMalloc of the decode workspace failed: ") + hipGetErrorString(e);
+    return bail(LKV_ERR_DEVICE);
+  }
+  c->ws_bytes = kDefaultDecodeWorkspace;
   *out = c;
   return LKV_OK;
 }
@@ -527,7 +538,26 @@ lkv_status lkv_layer_residency(const lkv_ctx *c, int64_t seq, int32_t layer, int
   if (!c) return LKV_ERR_INVALID_ARG;
   if (bad_layer(c, layer) || !out) return fail(c, LKV_ERR_INVALID_ARG, "lkv_layer_residency: bad argument");
   auto it = c->layers.find({seq, layer});
-  *out = it == c->layers.end() ? (int32_t)LKV_RES_NONE : it->second.residency;
+  int32_t res = it == c->layers.end() ? (int32_t)LKV_RES_NONE : it->second.residency;
+  if (!c->logical_only && (res == LKV_RES_HOST || res == LKV_RES_GPU)) {
+    // a host layer whose copy out (or whose CPU copies behind the pinned ring) has not finished, a GPU layer whose
+    // reload has not finished: the transfer's event answers without blocking
+    const int32_t ev = res == LKV_RES_HOST ? LKV_EV_OFFLOADED : LKV_EV_RELOADED;
+    const size_t idx = (size_t)layer * 4 + ev;
+    bool pending = false;
+    if (c->event_recorded[idx]) {
+      const hipError_t q = hipEventQuery(c->events[idx]);
+      if (q == hipErrorNotReady) {
+        (void)hipGetLastError();
+        pending = true;
+      } else if (q != hipSuccess) {
+        return fail(c, LKV_ERR_DEVICE, "lkv_layer_residency: hipEventQuery failed: %s", hipGetErrorString(q));
+      }
+    }
+    if (!pending && res == LKV_RES_HOST && const_cast<lkv_ctx *>(c)->tier.running() && const_cast<lkv_ctx *>(c)->tier.busy_key(layer)) pending = true;
+    if (pending) res = LKV_RES_IN_FLIGHT;
+  }
+  *out = res;
   return LKV_OK;
 }
 
@@ -831,22 +861,35 @@ lkv_status lkv_paged_decode_attention(lkv_ctx *c, int32_t layer, const void *Q, 
   if (((uintptr_t)Q | (uintptr_t)O) & 15)
     return fail(c, LKV_ERR_INVALID_ARG, "lkv_paged_decode_attention: Q and O must be 16-byte aligned");
   hipStream_t s = (hipStream_t)stream;
+  const int64_t need = lkv::decode_workspace_bytes(c, num_seqs, max_blocks_per_seq);
+  if (need > c->ws_bytes)
+    return fail(c, LKV_ERR_INVALID_ARG,
+                "lkv_paged_decode_attention: %d sequences with tables of %d blocks need a split-K workspace of %lld bytes, "
+                "the context has %lld: call lkv_reserve_decode_workspace first (this call never allocates)",
+                num_seqs, max_blocks_per_seq, (long long)need, (long long)c->ws_bytes);
   if (lkv_status st = wait_event(c, layer, LKV_EV_RELOADED, s)) return st;
-  int64_t need = lkv::decode_workspace_bytes(c, num_seqs, max_blocks_per_seq);
-  if (need > c->ws_bytes) {
-    // Earlier launches may still read the old workspace: drain before replacing it.
-    LKV_HIP(c, hipDeviceSynchronize());
-    if (c->ws) LKV_HIP(c, hipFree(c->ws));
-    c->ws = nullptr;
-    c->ws_bytes = 0;
-    LKV_HIP(c, hipMalloc((void **)&c->ws, (size_t)need));
-    c->ws_bytes = need;
-  }
   hipEvent_t t0;
   if (lkv_status st = timed_begin(c, s, &t0)) return st;
   LKV_HIP(c, lkv::launch_paged_decode(c, Q, O, block_table, max_blocks_per_seq, context_lens, num_seqs, c->ws, s));
   if (lkv_status st = timed_end(c, s, t0, 0, lkv_ctx::kTimedDecode)) return st;
   c->stats.decode_calls += 1;
+  return LKV_OK;
+}
+
+lkv_status lkv_reserve_decode_workspace(lkv_ctx *c, int32_t num_seqs, int32_t max_blocks_per_seq) {
+  if (!c) return LKV_ERR_INVALID_ARG;
+  if (c->logical_only) return fail(c, LKV_ERR_DEVICE, "lkv_reserve_decode_workspace: this context has no device resources (lkv_create_logical)");
+  if (num_seqs < 0 || max_blocks_per_seq < 0) return fail(c, LKV_ERR_INVALID_ARG, "lkv_reserve_decode_workspace: bad count");
+  if (!lkv::decode_supported(c)) return fail(c, LKV_ERR_UNSUPPORTED, "lkv_reserve_decode_workspace: no decode kernel for this shape");
+  const int64_t need = lkv::decode_workspace_bytes(c, num_seqs, max_blocks_per_seq);
+  if (need <= c->ws_bytes) return LKV_OK;
+  LKV_HIP(c, hipSetDevice(c->device));
+  LKV_HIP(c, hipDeviceSynchronize());  // earlier launches may still use the old workspace
+  if (c->ws) LKV_HIP(c, hipFree(c->ws));
+  c->ws = nullptr;
+  c->ws_bytes = 0;
+  LKV_HIP(c, hipMalloc((void **)&c->ws, (size_t)need));
+  c->ws_bytes = need;
   return LKV_OK;
 }
 
@@ -872,28 +915,6 @@ lkv_status lkv_set_profiling(lkv_ctx *c, int32_t on) {
   if (!c) return LKV_ERR_INVALID_ARG;
   if (c->logical_only) return fail(c, LKV_ERR_DEVICE, "lkv_set_profiling: this context has no device resources");
   c->profiling = on != 0;
-  return LKV_OK;
-}
-
-lkv_status lkv_probe_mfma_rate(lkv_ctx *c, double millis, int32_t random_operands, double *tflops, double *clock_mhz,
-                               void *stream) {
-  if (!c || !tflops || !clock_mhz) return LKV_ERR_INVALID_ARG;
-  if (c->logical_only) return fail(c, LKV_ERR_DEVICE, "lkv_probe_mfma_rate: this context has no device resources");
-  LKV_HIP(c, hipSetDevice(c->device));
-  LKV_HIP(c, lkv::probe_mfma_rate(millis, random_operands, tflops, clock_mhz, (hipStream_t)stream));
-  return LKV_OK;
-}
-
-lkv_status lkv_probe_clock_trace(lkv_ctx *c, int64_t *out, int32_t n, int32_t gap_cycles, int32_t *wall_clock_khz,
-                                 void *stream) {
-  if (!c || !out || !wall_clock_khz) return LKV_ERR_INVALID_ARG;
-  if (c->logical_only) return fail(c, LKV_ERR_DEVICE, "lkv_probe_clock_trace: this context has no device resources");
-  if (n < 1 || n > (1 << 20) || gap_cycles < 0 || gap_cycles > (1 << 24))
-    return fail(c, LKV_ERR_INVALID_ARG, "lkv_probe_clock_trace: n or gap_cycles out of range");
-  LKV_HIP(c, hipSetDevice(c->device));
-  int khz = 0;
-  LKV_HIP(c, lkv::probe_clock_trace((long long *)out, n, gap_cycles, &khz, (hipStream_t)stream));
-  *wall_clock_khz = khz;
   return LKV_OK;
 }
 

@@ -147,8 +147,4 @@ hipError_t launch_prefill(const lkv_ctx *c, const void *Q, const void *K, const 
                           int32_t causal, hipStream_t s);
 bool prefill_supported(const lkv_ctx *c);
 
-// Sustained bf16 MFMA rate and shader clock of the current device (measurement helper).
-hipError_t probe_mfma_rate(double millis, int random_operands, double *tflops, double *clock_mhz, hipStream_t s);
-hipError_t probe_clock_trace(long long *out_dev, int n, int gap_cycles, int *wall_khz, hipStream_t s);
-
 }  // namespace lkv

@@ -47,15 +47,32 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
   return __builtin_bit_cast(unsigned, v);
 }
 
+// Sequence s of the batch as the kernels use it: tokens t0 .. t0 + n - 1 of the packed tensors.  cu_seqlens lives in
+// device memory, where the host cannot check it; whatever it holds, 0 <= t0, 0 <= n <= max_seqlen and
+// t0 + n <= total_tokens come out of here, so that no row outside Q, K, V and O is ever addressed (a wrong entry gives
+// wrong or unwritten rows, not a fault).
+__device__ __forceinline__ void seq_range(const int32_t *__restrict__ cu_seqlens, int s, int total_tokens, int max_seqlen,
+                                          int &t0, int &n) {
+  const int a = min(max(cu_seqlens[s], 0), total_tokens);
+  const int b = min(max(cu_seqlens[s + 1], a), total_tokens);
+  t0 = a;
+  n = min(b - a, max_seqlen);
+}
+__device__ __forceinline__ int seq_len(const int32_t *__restrict__ cu_seqlens, int s, int total_tokens, int max_seqlen) {
+  int t0, n;
+  seq_range(cu_seqlens, s, total_tokens, max_seqlen, t0, n);
+  return n;
+}
+
 // Work slot k of a head -> (sequence, index of the tile pair inside it).  A sequence of n tokens owns ceil(n / 256)
 // consecutive slots (one per pair of 128-query tiles).  Up to 64 sequences are taken LONGEST FIRST (ties in batch
 // order), so that the long workgroups of an unequal batch start first and the short ones fill the end of the launch;
 // larger batches keep the batch order.  Every wavefront rebuilds the list from cu_seqlens.  Returns false when k is
 // past the last slot.
-__device__ __forceinline__ bool find_pair_slot(const int32_t *__restrict__ cu_seqlens, int num_seqs, int k, int lane,
-                                               int &seq, int &pidx) {
+__device__ __forceinline__ bool find_pair_slot(const int32_t *__restrict__ cu_seqlens, int num_seqs, int total_tokens,
+                                               int max_seqlen, int k, int lane, int &seq, int &pidx) {
   if (num_seqs <= 64) {
-    const int cnt = lane < num_seqs ? (cu_seqlens[lane + 1] - cu_seqlens[lane] + 255) / 256 : 0;
+    const int cnt = lane < num_seqs ? (seq_len(cu_seqlens, lane, total_tokens, max_seqlen) + 255) / 256 : 0;
     int pos = 0;  // slots of the sequences that come before this lane's in the longest-first order
     for (int t = 0; t < num_seqs; ++t) {
       const int ct = __builtin_amdgcn_readlane(cnt, t);
@@ -71,7 +88,7 @@ __device__ __forceinline__ bool find_pair_slot(const int32_t *__restrict__ cu_se
   int base = 0;
   for (int s0 = 0; s0 < num_seqs; s0 += 64) {
     const int s = s0 + lane;
-    const int cnt = s < num_seqs ? (cu_seqlens[s + 1] - cu_seqlens[s] + 255) / 256 : 0;
+    const int cnt = s < num_seqs ? (seq_len(cu_seqlens, s, total_tokens, max_seqlen) + 255) / 256 : 0;
     int inc = cnt;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -98,7 +115,7 @@ template <int D, bool CAUSAL, int QB>
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 prefill_bf16_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
                      uint16_t *__restrict__ O, const int32_t *__restrict__ cu_seqlens, int Hq, int Hkv,
-                     int tiles_per_seq, int total_wgs, float scale_log2e) {
+                     int tiles_per_seq, int total_wgs, int total_tokens, int max_seqlen, float scale_log2e) {
   constexpr int WQ = 32 * QB;        // queries per wavefront
   constexpr int BMQ = 4 * WQ;        // queries per workgroup
   constexpr int KS_STRIDE = D + 8, VT_STRIDE = BN + 4, OS_STRIDE = D + 8;
@@ -118,7 +135,8 @@ prefill_bf16_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__
   const int qt = tiles_per_seq - 1 - blockIdx.x % tiles_per_seq;
   const int rest = blockIdx.x / tiles_per_seq;
   const int h = rest % Hq, s = rest / Hq;
-  const int t0 = cu_seqlens[s], n = cu_seqlens[s + 1] - t0;
+  int t0, n;
+  seq_range(cu_seqlens, s, total_tokens, max_seqlen, t0, n);
   const int q0 = qt * BMQ;
   if (q0 >= n) return;
 
@@ -379,7 +397,7 @@ template <bool CAUSAL>
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 prefill_bf16_d128_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
                          uint16_t *__restrict__ O, const int32_t *__restrict__ cu_seqlens, int Hq, int Hkv,
-                         int num_seqs, int xcd_heads, float scale_log2e) {
+                         int num_seqs, int xcd_heads, int total_tokens, int max_seqlen, float scale_log2e) {
   constexpr int D = 128, UK = 32, KR = 4, VR = 4, TB = UK * D * 2, VOFF = KR * TB;
   constexpr int BMQ = 128, WQ = 32, OS_STRIDE = D + 8;
   __shared__ __attribute__((aligned(1024))) char smem[(KR + VR) * TB];
@@ -405,8 +423,9 @@ prefill_bf16_d128_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restr
     k = blockIdx.x / Hq;
   }
   int s, pidx;
-  if (!find_pair_slot(cu_seqlens, num_seqs, k, lane, s, pidx)) return;
-  const int t0 = cu_seqlens[s], n = cu_seqlens[s + 1] - t0;
+  if (!find_pair_slot(cu_seqlens, num_seqs, total_tokens, max_seqlen, k, lane, s, pidx)) return;
+  int t0, n;
+  seq_range(cu_seqlens, s, total_tokens, max_seqlen, t0, n);
   const int tiles_per_seq = (n + BMQ - 1) / BMQ;
 
   const int tid = threadIdx.x, ql = lane & 31, hh = lane >> 5;
@@ -689,12 +708,14 @@ prefill_bf16_d128_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restr
 template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(kThreads)
 prefill_f32_kernel(const float *__restrict__ Q, const float *__restrict__ K, const float *__restrict__ V,
-                   float *__restrict__ O, const int32_t *__restrict__ cu_seqlens, int Hq, int Hkv, float scale) {
+                   float *__restrict__ O, const int32_t *__restrict__ cu_seqlens, int Hq, int Hkv, int total_tokens,
+                   int max_seqlen, float scale) {
   constexpr int QB = 64, KB = 32, C = D / 4;
   __shared__ float Ks[KB][D + 4];
   __shared__ float Vs[KB][D + 4];
   const int s = blockIdx.z, h = blockIdx.y, q0 = blockIdx.x * QB;
-  const int t0 = cu_seqlens[s], n = cu_seqlens[s + 1] - t0;
+  int t0, n;
+  seq_range(cu_seqlens, s, total_tokens, max_seqlen, t0, n);
   if (q0 >= n) return;
   const int g = h / (Hq / Hkv);
   const int tid = threadIdx.x, qi = tid / 4, part = tid % 4;
@@ -760,16 +781,18 @@ hipError_t launch_bf16_d128(const lkv_ctx *c, const void *Q, const void *K, cons
   dim3 grid((unsigned)grid_wgs);
   if (causal)
     launch_timed(c, true, true, prefill_bf16_d128_kernel<true>, grid, dim3(kThreads), s, (const uint16_t *)Q,
-                       (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, cu, Hq, Hkv, num_seqs, xcd_heads, sl2);
+                       (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, cu, Hq, Hkv, num_seqs, xcd_heads, (int)total_tokens,
+                       max_seqlen, sl2);
   else
     launch_timed(c, true, true, prefill_bf16_d128_kernel<false>, grid, dim3(kThreads), s, (const uint16_t *)Q,
-                       (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, cu, Hq, Hkv, num_seqs, xcd_heads, sl2);
+                       (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, cu, Hq, Hkv, num_seqs, xcd_heads, (int)total_tokens,
+                       max_seqlen, sl2);
   return hipGetLastError();
 }
 
 template <int D>
 hipError_t launch_bf16(const lkv_ctx *c, const void *Q, const void *K, const void *V, void *O, const int32_t *cu,
-                       int num_seqs, int max_seqlen, int causal, hipStream_t s) {
+                       int num_seqs, int max_seqlen, int64_t total_tokens, int causal, hipStream_t s) {
   constexpr int QB = 1, BMQ = 128 * QB;
   // the kernel addresses a sequence's K/V rows with 32-bit byte offsets
   if ((int64_t)max_seqlen * c->cfg.num_kv_heads * D * 2 >= ((int64_t)1 << 32)) return hipErrorInvalidValue;
@@ -781,24 +804,26 @@ hipError_t launch_bf16(const lkv_ctx *c, const void *Q, const void *K, const voi
   if (causal)
     launch_timed(c, true, true, prefill_bf16_kernel<D, true, QB>, grid, dim3(kThreads), s, (const uint16_t *)Q,
                        (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, cu, c->cfg.num_q_heads,
-                       c->cfg.num_kv_heads, tiles, (int)total, sl2);
+                       c->cfg.num_kv_heads, tiles, (int)total, (int)total_tokens, max_seqlen, sl2);
   else
     launch_timed(c, true, true, prefill_bf16_kernel<D, false, QB>, grid, dim3(kThreads), s, (const uint16_t *)Q,
                        (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, cu, c->cfg.num_q_heads,
-                       c->cfg.num_kv_heads, tiles, (int)total, sl2);
+                       c->cfg.num_kv_heads, tiles, (int)total, (int)total_tokens, max_seqlen, sl2);
   return hipGetLastError();
 }
 
 template <int D>
 hipError_t launch_f32(const lkv_ctx *c, const void *Q, const void *K, const void *V, void *O, const int32_t *cu,
-                      int num_seqs, int max_seqlen, int causal, hipStream_t s) {
+                      int num_seqs, int max_seqlen, int64_t total_tokens, int causal, hipStream_t s) {
   dim3 grid((unsigned)((max_seqlen + 63) / 64), (unsigned)c->cfg.num_q_heads, (unsigned)num_seqs);
   if (causal)
     launch_timed(c, true, true, prefill_f32_kernel<D, true>, grid, dim3(kThreads), s, (const float *)Q, (const float *)K,
-                       (const float *)V, (float *)O, cu, c->cfg.num_q_heads, c->cfg.num_kv_heads, c->scale);
+                       (const float *)V, (float *)O, cu, c->cfg.num_q_heads, c->cfg.num_kv_heads, (int)total_tokens, max_seqlen,
+                       c->scale);
   else
     launch_timed(c, true, true, prefill_f32_kernel<D, false>, grid, dim3(kThreads), s, (const float *)Q, (const float *)K,
-                       (const float *)V, (float *)O, cu, c->cfg.num_q_heads, c->cfg.num_kv_heads, c->scale);
+                       (const float *)V, (float *)O, cu, c->cfg.num_q_heads, c->cfg.num_kv_heads, (int)total_tokens, max_seqlen,
+                       c->scale);
   return hipGetLastError();
 }
 
@@ -810,11 +835,12 @@ bool prefill_supported(const lkv_ctx *c) { return c->cfg.head_dim == 64 || c->cf
 
 hipError_t launch_prefill(const lkv_ctx *c, const void *Q, const void *K, const void *V, void *O, const int32_t *cu,
                           int32_t num_seqs, int32_t max_seqlen, int64_t total_tokens, int32_t causal, hipStream_t s) {
-  if (c->cfg.num_q_heads > 65535 || num_seqs > 65535) return hipErrorInvalidValue;
+  // token offsets are 32-bit in cu_seqlens and in the kernels
+  if (c->cfg.num_q_heads > 65535 || num_seqs > 65535 || total_tokens > INT32_MAX) return hipErrorInvalidValue;
   if (c->cfg.dtype == LKV_F32)
-    return c->cfg.head_dim == 64 ? launch_f32<64>(c, Q, K, V, O, cu, num_seqs, max_seqlen, causal, s)
-                                 : launch_f32<128>(c, Q, K, V, O, cu, num_seqs, max_seqlen, causal, s);
-  return c->cfg.head_dim == 64 ? launch_bf16<64>(c, Q, K, V, O, cu, num_seqs, max_seqlen, causal, s)
+    return c->cfg.head_dim == 64 ? launch_f32<64>(c, Q, K, V, O, cu, num_seqs, max_seqlen, total_tokens, causal, s)
+                                 : launch_f32<128>(c, Q, K, V, O, cu, num_seqs, max_seqlen, total_tokens, causal, s);
+  return c->cfg.head_dim == 64 ? launch_bf16<64>(c, Q, K, V, O, cu, num_seqs, max_seqlen, total_tokens, causal, s)
                                : launch_bf16_d128(c, Q, K, V, O, cu, num_seqs, max_seqlen, total_tokens, causal, s);
 }
 

@@ -161,6 +161,27 @@ def normal_tensor(rng: np.random.Generator, shape: Sequence[int], scale: float, 
     return x if dtype == "f32" else f32_to_bf16_bits(x)   # also for "fp8": only the pool is 8-bit
 
 
+def normal_tensor_chunked(config_number: int, stream: str, index: int, shape: Sequence[int], scale: float,
+                          dtype: str, rows_per_chunk: int = 4096, threads: int = 16) -> np.ndarray:
+    """The same kind of tensor for sizes where one generator would take minutes (GiB-sized caches): rows
+    [c * rows_per_chunk, (c + 1) * rows_per_chunk) come from the child stream (stream, index, c), so the result does
+    not depend on how many threads draw the chunks."""
+    from concurrent.futures import ThreadPoolExecutor
+    shape = tuple(shape)
+    out = np.empty(shape, dtype=np.float32 if dtype == "f32" else np.uint16)
+    pos = STREAMS.index(stream)
+
+    def draw(c: int) -> None:
+        a, b = c * rows_per_chunk, min(shape[0], (c + 1) * rows_per_chunk)
+        child = np.random.SeedSequence(SEED_BASE + config_number, spawn_key=(pos, index, c))
+        out[a:b] = normal_tensor(np.random.Generator(np.random.PCG64(child)), (b - a,) + shape[1:], scale, dtype)
+
+    chunks = range(-(-shape[0] // rows_per_chunk))
+    with ThreadPoolExecutor(max_workers=max(1, threads)) as ex:
+        list(ex.map(draw, chunks))
+    return out
+
+
 def qkv(config_number: int, layer: int, num_tokens: int, shape: KVShape, scale: float,
         q_gain: float = 1.0) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     """Token-major Q [T][Hq][d], K and V [T][Hkv][d] for one layer (independent streams per layer)."""

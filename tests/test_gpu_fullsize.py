@@ -17,6 +17,11 @@ pytestmark = pytest.mark.gpu
 THREADS = 16
 
 
+def say(msg: str) -> None:
+    """Progress of the minute-long tests (seen with pytest -s; a silent GPU run is taken for a hung one)."""
+    print(f"[fullsize] {msg}", flush=True)
+
+
 def sampled_prefill_check(cfg, layer, Q, K, V, O_dev, lens, shape, scale, triples, rows_per=64):
     """>= 64 rows (always 0, 15, 16, n-1) for each of the given (sequence, head) pairs."""
     cu = wl.cu_seqlens(lens)
@@ -365,4 +370,162 @@ def test_workload5_mixed_iteration_through_the_ring_at_the_7b_shape():
     o.write_kv(K, V, np.concatenate([o.slot_mapping(i, 0, 0, n) for i, n in enumerate(plens)]))
     want = o.pack_layer_blocks(sum((o.block_table(i, 0) for i in range(len(plens))), []))
     assert it.prompt_images[0].tobytes() == want.tobytes(), "offload image of the new prompts, layer 0"
+    it.close()
+
+
+# ----------------------------------------------------------------------------- workload 3 as the config is written
+def test_workload3_batch_of_four_16k_prompts_offload_reload_and_64_decode_steps():
+    """Workload 3 through ``LayerKVEngine`` (the calls ``bench.py`` issues) at its own batch: FOUR 16384-token prompts
+    in one launch, three of the 32 layers carried through the whole life cycle: layer 3 is one the even spread of
+    Section 3.2.2 retains (24 of 32 offloaded keeps 3, 7, ..., 31), layers 4 and 30 are offloaded (a full 1 GiB image
+    each, compared byte for byte), freed, and reloaded into other blocks.  Then all 64 decode steps run on layers 3
+    and 30; the oracle checks the steps that open a new block (0 and 16), the one that fills it (15) and the last
+    (63): tables bit-exact after every crossing, every output row of the 4 x (16384 + step + 1) split decode.
+    The pool holds what these three layers need (the workload's 32 GiB pool adds nothing to the launches)."""
+    w = wl.workload(3)
+    sh, lens = w.shape, list(w.prompt_lens)
+    B, T, bs = len(lens), sum(lens), sh.block_size
+    retained = orc.retained_layers(sh.num_layers, sh.num_layers - len(w.offload_layers))
+    assert sorted(set(range(sh.num_layers)) - set(retained)) == list(w.offload_layers)
+    kept, gone = 3, (4, 30)
+    assert kept in retained and all(l in w.offload_layers for l in gone)
+    per_layer = sum(wl.blocks_for(n + w.decode_steps, bs) for n in lens)
+    nblk = 3 * per_layer + 512
+    order = wl.free_list_order(3, nblk, index=7)
+    pool = torch.zeros(nblk * sh.block_bytes, dtype=torch.uint8, device=H.DEV)
+    eng = LayerKVEngine(sh, nblk, order, pool=pool)
+    o = orc.LayerKVOracle(sh.num_layers, sh.num_q_heads, sh.num_kv_heads, sh.head_dim, bs, nblk, sh.dtype)
+    o.pool_reset(order)
+    eng.begin_prompts(lens)
+    layer_bytes = sum(wl.blocks_for(n, bs) for n in lens) * sh.block_bytes
+    assert layer_bytes == 1 << 30
+    pinned = {l: eng.pinned(layer_bytes) for l in gone}
+    for layer in (kept,) + gone:
+        Q = wl.normal_tensor_chunked(3, "q", layer, (T, sh.num_q_heads, sh.head_dim), w.data_scale, "bf16")
+        K = wl.normal_tensor_chunked(3, "k", layer, (T, sh.num_kv_heads, sh.head_dim), w.data_scale, "bf16")
+        V = wl.normal_tensor_chunked(3, "v", layer, (T, sh.num_kv_heads, sh.head_dim), w.data_scale, "bf16")
+        Qd, Kd, Vd = H.to_dev(Q), H.to_dev(K), H.to_dev(V)
+        Od = H.empty_like_storage(Q.shape, "bf16")
+        eng.prefill_layer(layer, Qd, Kd, Vd, Od, offload_to=pinned.get(layer))
+        for s, n in enumerate(lens):
+            o.alloc_layer_blocks(s, layer, n)
+            assert eng.ctx.get_block_table(s, layer).tolist() == o.block_table(s, layer)
+        o.write_kv(K, V, np.concatenate([o.slot_mapping(s, layer, 0, n) for s, n in enumerate(lens)]))
+        torch.cuda.synchronize()
+        # sampled rows of ALL FOUR sequences (two heads each): the work order of a batch of long prompts
+        sampled_prefill_check(3, layer, Q, K, V, Od, lens, sh, w.data_scale,
+                              [(s, h) for s in range(B) for h in ((5 * s + layer) % 32, 31 - s)], rows_per=40)
+        say(f"workload 3: layer {layer} prefilled, sampled rows of four prompts match")
+        if layer in gone:
+            eng.ctx.event_synchronize(layer, lkv.LKV_EV_OFFLOADED)
+            ids = sum((o.block_table(s, layer) for s in range(B)), [])
+            assert pinned[layer].numpy().tobytes() == o.pack_layer_blocks(ids).tobytes(), f"offload image, layer {layer}"
+        del Q, K, V, Qd, Kd, Vd, Od
+    # release both offloaded layers, let someone else take blocks in between, reload into whatever is free now
+    old = {l: sum((o.block_table(s, l) for s in range(B)), []) for l in gone}
+    for l in gone:
+        eng.release_offloaded(l)
+        for s in range(B):
+            o.free_layer_blocks(s, l, to_host=True)
+    eng.ctx.alloc_layer_blocks(999, 0, bs * 100)
+    o.alloc_layer_blocks(999, 0, bs * 100)
+    for l in gone:
+        eng.reload_layer(l)
+        for s, n in enumerate(lens):
+            o.alloc_layer_blocks(s, l, n)
+        new_ids = sum((o.block_table(s, l) for s in range(B)), [])
+        assert new_ids != old[l]
+        o.unpack_layer_blocks(new_ids, pinned[l].numpy())       # the image was shown equal to the oracle's above
+        torch.cuda.synchronize()
+        pool_blocks_equal(pool, o, new_ids, f"after reload, layer {l}")
+        say(f"workload 3: layer {l} offloaded (1 GiB image equal), reloaded into other blocks")
+    # 64 decode steps on the retained layer and on one reloaded layer
+    checked_steps = (0, 15, 16, 63)
+    for layer in (kept, 30):
+        for step in range(w.decode_steps):
+            q, k, v = wl.decode_qkv(3, layer, step, B, sh, w.data_scale, q_gain=8.0)
+            Od = H.empty_like_storage(q.shape, "bf16")
+            eng.decode_layer(layer, H.to_dev(q), H.to_dev(k), H.to_dev(v), Od, step=step)
+            slots = []
+            for s, n in enumerate(lens):
+                o.alloc_layer_blocks(s, layer, n + step + 1)
+                slots.append(o.slot_mapping(s, layer, n + step, 1))
+            o.write_kv(k, v, np.concatenate(slots))
+            if step % bs == 0 or step in checked_steps:       # a new block was opened (steps 0, 16, 32, 48)
+                for s in range(B):
+                    assert eng.ctx.get_block_table(s, layer).tolist() == o.block_table(s, layer), (layer, step, s)
+            if step in checked_steps:
+                bt = o.padded_block_table(range(B), layer)
+                ref = o.paged_decode_attention(q, bt, [n + step + 1 for n in lens], threads=THREADS)
+                torch.cuda.synchronize()
+                H.check_attention(H.to_host(Od, "bf16"), ref, "bf16", w.data_scale, f"decode layer {layer} step {step}")
+                say(f"workload 3: decode layer {layer} step {step} matches")
+        ids = sum((o.block_table(s, layer) for s in range(B)), [])
+        assert len(ids) == per_layer
+        torch.cuda.synchronize()
+        pool_blocks_equal(pool, o, ids, f"after 64 appended tokens, layer {layer}")
+    eng.close()
+
+
+# ----------------------------------------------------------------------------- workload 5 at all 64 sequences
+def test_workload5_all_64_decode_sequences_through_the_ring_every_row():
+    """The mixed iteration of workload 5 with ALL 64 decoding sequences (contexts 563..16227, 8.8 GiB of KV per
+    layer): the launch ``bench.py`` times (2048 (sequence, head) units x 4 partitions, plain work order, not the
+    longest-first list of small batches).  Three layers: layer 1 stays on the GPU, layers 0 and 2 live in ordinary
+    host memory and come back through a ring of ONE set of blocks (layer 2's reload takes the blocks layer 0's decode
+    has just released), the two 8192-token prompts prefill and leave alongside.  Every decode row of every layer is
+    compared with the oracle (per sequence: its tokens written into an oracle pool of its own, attended through the
+    oracle's table); the new prompts' offload images byte for byte; sampled causal rows of the prompts."""
+    from paper_2410_00428_amd.serving import MixedIteration
+    w = wl.workload(5)
+    bs = w.shape.block_size
+    L, host = 3, (0, 2)
+    sh = wl.KVShape(L, w.shape.num_q_heads, w.shape.num_kv_heads, w.shape.head_dim, bs, "bf16")
+    dlens, plens = list(w.decode_lens), list(w.prompt_lens)
+    B, Td, T = len(dlens), sum(dlens), sum(plens)
+    assert B == 64
+    dblk = sum(wl.blocks_for(n, bs) for n in dlens)
+    pblk = sum(wl.blocks_for(n, bs) for n in plens)
+    nblk = (L - len(host) + 1) * dblk + L * pblk + 64
+    it = MixedIteration(sh, dlens, plens, host, nblk, ring_layers=1, free_order=wl.free_list_order(5, nblk, index=5),
+                        tier_unit_bytes=64 << 20, tier_units=4, tier_threads=8)
+    scale = w.data_scale
+    A = wl.normal_tensor_chunked(5, "k", 950, (Td, sh.num_kv_heads, sh.head_dim), scale, "bf16")
+    Bt = wl.normal_tensor_chunked(5, "v", 950, (Td, sh.num_kv_heads, sh.head_dim), scale, "bf16")
+    kv_of = lambda l: (A, Bt) if l % 2 == 0 else (Bt, A)
+    Ad, Bd = H.to_dev(A), H.to_dev(Bt)
+    q_host = [wl.decode_qkv(5, l, 1, B, sh, scale, q_gain=0.25)[0] for l in range(L)]
+    q_dev = [H.to_dev(q) for q in q_host]
+    Q, K, V = wl.qkv(5, 951, T, sh, scale, q_gain=0.25)
+    Qd, Kd, Vd = H.to_dev(Q), H.to_dev(K), H.to_dev(V)
+    say("workload 5: inputs drawn and uploaded")
+    it.build_cached_state(lambda l: (Ad, Bd) if l % 2 == 0 else (Bd, Ad))
+    say("workload 5: cached state built (two layers in host memory)")
+    O_dec = H.empty_like_storage((L, B, sh.num_q_heads, sh.head_dim), "bf16")
+    O_dec.fill_(0x7FC0)
+    O_pf = [H.empty_like_storage(Q.shape, "bf16") for _ in range(L)]
+    it.run(q_dev, O_dec, lambda l: (Qd, Kd, Vd), O_pf)
+    it.finish()
+    got = H.to_host(O_dec, "bf16")
+    starts = np.concatenate([[0], np.cumsum(dlens)])
+    for s, n in enumerate(dlens):
+        o = orc.LayerKVOracle(1, sh.num_q_heads, sh.num_kv_heads, sh.head_dim, bs, wl.blocks_for(n, bs), "bf16")
+        o.pool_reset(np.random.default_rng(s).permutation(wl.blocks_for(n, bs)))
+        o.alloc_layer_blocks(0, 0, n)
+        slots, bt = o.slot_mapping(0, 0, 0, n), o.padded_block_table([0], 0)
+        for l in range(L):
+            k_l, v_l = kv_of(l)
+            o.write_kv(k_l[starts[s]:starts[s] + n], v_l[starts[s]:starts[s] + n], slots)
+            ref = o.paged_decode_attention(q_host[l][s:s + 1], bt, [n], threads=THREADS)
+            H.check_attention(got[l][s:s + 1], ref, "bf16", scale, f"decode layer {l} sequence {s} ({n} tokens)")
+        if s % 8 == 7:
+            say(f"workload 5: decode rows of sequences 0..{s} match in all three layers")
+    o = orc.LayerKVOracle(1, sh.num_q_heads, sh.num_kv_heads, sh.head_dim, bs, pblk, "bf16")
+    for i, n in enumerate(plens):
+        o.alloc_layer_blocks(i, 0, n)
+    o.write_kv(K, V, np.concatenate([o.slot_mapping(i, 0, 0, n) for i, n in enumerate(plens)]))
+    want = o.pack_layer_blocks(sum((o.block_table(i, 0) for i in range(len(plens))), [])).tobytes()
+    for l in host:
+        assert it.prompt_images[l].tobytes() == want, f"offload image of the new prompts, layer {l}"
+        sampled_prefill_check(5, l, Q, K, V, O_pf[l], plens, sh, scale, [(0, 7), (1, 24)], rows_per=32)
     it.close()

@@ -91,7 +91,8 @@ class Scenario:
             assert ids.tolist() == self.o.block_table(s, layer)
             self.c.unpack_layer_blocks(layer, ids, images[s][0], stream)
             self.o.unpack_layer_blocks(ids, images[s][1])
-            assert self.c.layer_residency(s, layer) == lkv.LKV_RES_GPU
+            # the reload has just been queued: its blocks are the layer's, the data may still be on its way
+            assert self.c.layer_residency(s, layer) in (lkv.LKV_RES_GPU, lkv.LKV_RES_IN_FLIGHT)
 
     def decode_step(self, layer, step=0, append=True, stream=None):
         sh = self.shape
@@ -386,6 +387,114 @@ def test_decode_zero_context_and_poisoned_unused_slots():
     sc.close()
 
 
+@pytest.mark.parametrize("shape", [wl.KVShape(1, 8, 8, 128, 16, "bf16"), wl.KVShape(1, 4, 2, 128, 16, "bf16"),
+                                   wl.KVShape(1, 4, 2, 64, 16, "bf16"), wl.KVShape(1, 2, 2, 64, 16, "f32")])
+def test_prefill_stays_inside_its_tensors_whatever_cu_seqlens_holds(shape):
+    """cu_seqlens lives in device memory, where the host cannot check it.  The kernels cut every sequence to the
+    total_tokens rows the four tensors have and to max_seqlen tokens: with an entry far past the end, one out of
+    order and a negative one, nothing outside the tensors is written (guard rows in front of and behind O keep
+    their pattern; Q, K and V are interior slices of larger tensors, so a read a little outside them would not be
+    seen, but one at the offsets these entries name would leave the allocation), sequences whose entries are
+    right still match the oracle, and a max_seqlen below a real length leaves the rows past it unwritten."""
+    T, G = 700, 64                                   # tokens, guard rows on each side
+    dt = shape.dtype
+    Q, K, V = wl.qkv(31, 0, T, shape, 1.0)
+    fill = 0x7FC0 if dt == "bf16" else float("nan")
+
+    def framed(a):
+        t = H.empty_like_storage((T + 2 * G,) + a.shape[1:], dt)
+        t.fill_(fill)
+        t[G:G + T] = H.to_dev(a)
+        return t
+    Qf, Kf, Vf = framed(Q), framed(K), framed(V)
+    c = lkv.LKV(1, shape.num_q_heads, shape.num_kv_heads, shape.head_dim, 16, 4, dt)
+
+    def run(cu, max_seqlen):
+        Of = H.empty_like_storage((T + 2 * G, shape.num_q_heads, shape.head_dim), dt)
+        Of.fill_(fill)
+        c.prefill_attention(0, Qf[G:], Kf[G:], Vf[G:], Of[G:], H.to_dev(np.asarray(cu, dtype=np.int32)), len(cu) - 1,
+                            max_seqlen, T, True)
+        torch.cuda.synchronize()
+        raw = Of.cpu().numpy()
+        pat = np.uint16(0x7FC0).view(np.int16) if dt == "bf16" else None
+        for part in (raw[:G], raw[G + T:]):
+            assert (part == pat).all() if dt == "bf16" else np.isnan(part).all(), "a guard row was written"
+        return raw[G:G + T]
+
+    good = np.asarray([0, 300, 301, 700], dtype=np.int32)
+    ref = orc.prefill_attention(Q, K, V, good, dt, threads=ORC_THREADS)
+    # last entry far past the end: the last sequence is cut to the rows that exist, the others are untouched
+    got = run([0, 300, 301, 700 + 100000], 512)
+    widen = (lambda a: wl.bf16_bits_to_f32(a.view(np.uint16))) if dt == "bf16" else (lambda a: a)
+    H.check_attention(widen(got), ref, dt, 1.0, "last entry past the end")
+    # an entry past the end, one out of order and a negative one: sequence 1 is cut at the last row, sequences 2 and
+    # 3 come out empty, so the launch computes what the oracle computes for the two sequences [0, 300) and [300, 700)
+    got = run([0, 300, 700 + 5000, 650, -7], 512)
+    ref2 = orc.prefill_attention(Q, K, V, np.asarray([0, 300, 700], dtype=np.int32), dt, threads=ORC_THREADS)
+    H.check_attention(widen(got), ref2, dt, 1.0, "broken entries behind two good sequences")
+    # max_seqlen below a real length: the rows past it stay unwritten, the rows before it are right
+    got = run(good, 256)
+    H.check_attention(widen(got[:256]), ref[:256], dt, 1.0, "rows below max_seqlen")
+    tail = got[256:300]
+    assert (tail == np.uint16(0x7FC0).view(np.int16)).all() if dt == "bf16" else np.isnan(tail).all()
+    c.destroy()
+
+
+def test_decode_never_allocates_and_reserve_grows_the_workspace():
+    """lkv_paged_decode_attention uses the workspace the context has: a launch that needs more is refused with an
+    error that names lkv_reserve_decode_workspace, and runs once that call has made room.  The host sizes the split
+    from the table WIDTH, so wide tables over a small pool are enough to need more than the 32 MiB of lkv_create."""
+    shape = wl.KVShape(1, 64, 8, 128, 16, "bf16")
+    B, width, nblk = 256, 1024, 64
+    sc = Scenario(33, shape, (200, 90), nblk)
+    sc.prefill_layer(0, check_attn=False)
+    rows = [sc.c.get_block_table(s % 2, 0) for s in range(B)]
+    bt = np.full((B, width), -1, dtype=np.int32)
+    for i, r in enumerate(rows):
+        bt[i, :len(r)] = r
+    ctx = np.asarray([(200, 90)[s % 2] for s in range(B)], dtype=np.int32)
+    q = wl.normal_tensor(np.random.default_rng(33), (B, 64, 128), 1.0, "bf16")
+    Od = H.empty_like_storage(q.shape, "bf16")
+    args = (0, H.to_dev(q), Od, H.to_dev(bt), width, H.to_dev(ctx), B)
+    with pytest.raises(lkv.LkvError) as e:
+        sc.c.paged_decode_attention(*args)
+    assert e.value.status == lkv.LKV_ERR_INVALID_ARG and "lkv_reserve_decode_workspace" in str(e.value)
+    sc.c.reserve_decode_workspace(B, width)
+    sc.c.paged_decode_attention(*args)
+    torch.cuda.synchronize()
+    ref = sc.o.paged_decode_attention(q, bt, ctx, threads=ORC_THREADS)
+    H.check_attention(H.to_host(Od, "bf16"), ref, "bf16", 1.0, "decode after reserve")
+    sc.c.reserve_decode_workspace(1, 1)     # never shrinks: the same launch still runs
+    sc.c.paged_decode_attention(*args)
+    torch.cuda.synchronize()
+    sc.close()
+
+
+def test_residency_reports_a_transfer_in_flight():
+    """Section 3.2.2's location of a layer has a third answer while a transfer this context queued is running:
+    a 256 MiB image takes milliseconds on the host link, the query right behind the call finds it unfinished."""
+    shape = wl.KVShape(2, 32, 32, 128, 16, "bf16")
+    n = 1024 * 16
+    c = lkv.LKV(2, 32, 32, 128, 16, 2048 + 8, "bf16")
+    c.alloc_layer_blocks(0, 1, n)
+    assert c.layer_residency(0, 1) == lkv.LKV_RES_GPU and c.layer_residency(0, 0) == lkv.LKV_RES_NONE
+    ids = c.get_block_table(0, 1)
+    buf = H.pinned_bytes(len(ids) * shape.block_bytes)
+    side = torch.cuda.Stream()
+    c.pack_layer_blocks(1, ids, buf, side)
+    c.stream_wait_event(1, lkv.LKV_EV_PACKED, side)
+    c.free_layer_blocks(0, 1, True)
+    assert c.layer_residency(0, 1) == lkv.LKV_RES_IN_FLIGHT          # the copy out is still running
+    c.event_synchronize(1, lkv.LKV_EV_OFFLOADED)
+    assert c.layer_residency(0, 1) == lkv.LKV_RES_HOST
+    c.alloc_layer_blocks(0, 1, n)
+    c.unpack_layer_blocks(1, c.get_block_table(0, 1), buf, side)
+    assert c.layer_residency(0, 1) == lkv.LKV_RES_IN_FLIGHT          # the reload is on its way
+    c.event_synchronize(1, lkv.LKV_EV_RELOADED)
+    assert c.layer_residency(0, 1) == lkv.LKV_RES_GPU
+    c.destroy()
+
+
 # ----------------------------------------------------------------------------- copies: edge cases
 def test_write_kv_negative_slots_and_empty_calls():
     shape = wl.KVShape(1, 2, 2, 64, 16, "bf16")
@@ -488,38 +597,6 @@ def test_offload_on_side_stream_overlapping_next_layers_compute():
         sc.decode_step(layer, stream=main)
     sc.check_pool("after overlapped offload/reload")
     sc.close()
-
-
-def test_clock_trace_is_monotonic_and_reads_a_plausible_shader_clock():
-    shape = wl.KVShape(1, 2, 2, 64, 16, "bf16")
-    c, o, pool = H.make_pair(shape, 4)
-    n = 64
-    out = torch.zeros(2 * n, dtype=torch.int64, device=H.DEV)
-    khz = c.probe_clock_trace(out, n, 20000)
-    torch.cuda.synchronize()
-    a = out.cpu().numpy().reshape(n, 2)
-    assert 1000 <= khz <= 1000000
-    assert (np.diff(a[:, 0]) > 0).all() and (np.diff(a[:, 1]) > 0).all()
-    mhz = np.diff(a[:, 1]) / np.diff(a[:, 0]) * (khz / 1000.0)
-    assert 100.0 < np.median(mhz) < 3000.0, mhz
-    with pytest.raises(lkv.LkvError):
-        c.probe_clock_trace(out, 0, 20000)
-    c.destroy()
-
-
-def test_mfma_probe_reports_a_plausible_rate_and_clock():
-    """Measurement helper: the sustained MFMA rate equals 4 SIMDs x 1024 flop/clock x CUs x measured clock
-    (the stream keeps the pipes full), and constant operands never run slower than random ones."""
-    c = lkv.LKV(1, 4, 4, 128, 16, 8, "bf16")
-    tf_r, mhz_r = c.probe_mfma_rate(5.0, True)
-    tf_c, mhz_c = c.probe_mfma_rate(5.0, False)
-    cus = torch.cuda.get_device_properties(0).multi_processor_count
-    for tf, mhz in ((tf_r, mhz_r), (tf_c, mhz_c)):
-        assert 500.0 < mhz < 3000.0
-        pipe_rate = cus * 4 * 1024 * mhz * 1e6 / 1e12
-        assert 0.85 * pipe_rate < tf < 1.02 * pipe_rate, (tf, mhz, pipe_rate)
-    assert tf_c > 0.9 * tf_r
-    c.destroy()
 
 
 # ----------------------------------------------------------------------------- pageable host tier

@@ -82,6 +82,7 @@ def test_mixed_iteration_host_layers_through_a_ring_of_blocks_and_the_pageable_t
         return pool.view(nblk, -1)[torch.from_numpy(np.asarray(ids, dtype=np.int64)).to(H.DEV)].cpu().numpy().tobytes()
 
     it.build_cached_state(lambda l: (H.to_dev(kv[l][0]), H.to_dev(kv[l][1])))
+    torch.cuda.synchronize()
     for l in host:
         same = same_tokens(it.images[l].tobytes(), o.pack_layer_blocks(o_ids(range(B), l)).tobytes(), dlens, sh)
         assert same, f"host image of layer {l}"

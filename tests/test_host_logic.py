@@ -48,6 +48,11 @@ def test_device_calls_fail_loudly_on_a_logical_context():
     assert e.value.status == lkv.LKV_ERR_DEVICE
     with pytest.raises(lkv.LkvError):
         c.paged_decode_attention(0, 0, 0, 0, 0, 0, 0)
+    for call in (lambda: c.reserve_decode_workspace(4, 64),):
+        with pytest.raises(lkv.LkvError) as e:
+            call()
+        assert e.value.status == lkv.LKV_ERR_DEVICE
+    assert c.layer_residency(0, 0) == lkv.LKV_RES_NONE      # a logical context has no transfers: never IN_FLIGHT
 
 
 def test_random_op_sequence_matches_oracle_bit_for_bit():
