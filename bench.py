@@ -65,6 +65,9 @@ def parse_args():
                          "decode sequences), with a step of workloads 3 and 2 as components; 2 or 3: that workload alone")
     ap.add_argument("--no-components", action="store_true",
                     help="workload 5 only: skip the steps of workloads 3 and 2 that the line carries as components")
+    ap.add_argument("--component", action="store_true",
+                    help="workloads 2 and 3: print the cut of the figures that the default line carries for them (what "
+                         "the default run asks of its child processes)")
     ap.add_argument("--component-steps", type=int, default=0,
                     help="timed steps of the workload 3 / workload 2 components (0: 2 resp. 5)")
     ap.add_argument("--decode-seqs", type=int, default=64, help="workload 5: decoding sequences (64 = the full size)")
@@ -441,17 +444,31 @@ def main():
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
     if args.workload != 5:
-        print(json.dumps(prefill_decode_workload(args, args.workload, args.steps, args.warmup, component=False)))
+        full = prefill_decode_workload(args, args.workload, args.steps, args.warmup, component=args.component)
+        if args.component:
+            full = {k: full[k] for k in ("config", "steps", "warmup", "ms_per_step", "components", "overlap",
+                                         "kernels_alone", "roofline", "rooflines_other")}
+        print(json.dumps(full))
         return
-    out = mixed_iteration(args)
+    # A full step of the two prefill-heavy configurations, so that the same line carries the 16k-token prefill, the
+    # 64-step split decode and the offload / reload of whole layers.  Each runs in a process of its own BEFORE this
+    # process touches the GPU (one process on the card at a time): a component then measures what `--workload N`
+    # alone measures, whatever the 200 GiB of host memory of the main workload leave behind in this process.
+    parts = {}
     if not args.no_components and args.kv_dtype == "bf16":
-        # a full step of the two prefill-heavy configurations, so that the same line carries the 16k-token prefill,
-        # the 64-step split decode and the offload / reload of whole layers
-        for number, steps, warmup in ((3, args.component_steps or 2, 1), (2, args.component_steps or 5, 2)):
+        import subprocess
+        for number, steps, warmup in ((2, args.component_steps or 5, 2), (3, args.component_steps or 2, 1)):
             print(f"[bench] component: workload {number}, {warmup} warm-up + {steps} timed steps", file=sys.stderr, flush=True)
-            full = prefill_decode_workload(args, number, steps, warmup, component=True)
-            out[f"workload{number}"] = {k: full[k] for k in ("config", "steps", "warmup", "ms_per_step", "components",
-                                                            "overlap", "kernels_alone", "roofline", "rooflines_other")}
+            cmd = [sys.executable, os.path.abspath(__file__), "--workload", str(number), "--steps", str(steps),
+                   "--warmup", str(warmup), "--component", "--no-cpu-baseline", "--no-extras"]
+            r = subprocess.run(cmd, stdout=subprocess.PIPE, text=True)
+            lines = [ln for ln in r.stdout.splitlines() if ln.startswith("{")]
+            if r.returncode != 0 or not lines:
+                print(f"bench.py: the workload {number} component failed (exit {r.returncode})", file=sys.stderr)
+                sys.exit(r.returncode or 1)
+            parts[f"workload{number}"] = json.loads(lines[-1])
+    out = mixed_iteration(args)
+    out.update(parts)
     print(json.dumps(out))
 
 

@@ -425,13 +425,29 @@ template <int T> __device__ __forceinline__ unsigned bf16_pair(u32x2 w) {
   return __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[T >> 1], 1.0f, (T & 1) != 0));
 }
 
+// How the workgroups of a launch find their work.
+enum DecodeOrder {
+  kOrderPlain = 0,    // workgroup rank -> (sequence, partition), sequence fastest
+  kOrderLongest = 1,  // the launch's (sequence, partition) items longest first (decode_work_item)
+  kOrderEven = 2      // every workgroup takes the same number of key pairs, whatever sequences they belong to
+};
+constexpr int kMaxEvenSeqs = 256;  // batch size up to which the even split is built
+// Even split: what one (sequence, kv head) row costs on the line of work, in units of one key pair: its pairs plus
+// kRowCost for starting and finishing a piece (first table entries and keys behind dependent loads, the merge of the
+// wavefronts: a few microseconds, against ~0.7 us of streaming per pair at a CU's share of the HBM rate; 8 measured
+// best among 4, 8 and 12).
+constexpr int kRowCost = 8;
+__device__ __forceinline__ int even_row_cost(int tokens) {
+  return tokens > 0 ? (tokens + 2 * kBlock - 1) / (2 * kBlock) + kRowCost : 0;
+}
+
 template <int G, int WAVES, bool FP8>
-__global__ void __launch_bounds__(WAVES * 64)
+__global__ void __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))  // two wavefronts per SIMD
 paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, const char *__restrict__ pool,
                          const int32_t *__restrict__ block_table, int max_blocks,
                          const int32_t *__restrict__ context_lens, int Hq, int group, int64_t block_bytes,
                          int pool_blocks, float scale, float out_scale, int partition, int num_parts, int num_seqs,
-                         int lpt_order, Workspace ws) {
+                         int order, Workspace ws) {
   // G is the capacity (LDS rows of the merge) for `group` <= G query heads per kv head: the heads are columns of
   // the matrix products, of which there are 16 whatever the group size.
   // FP8: the pool holds one-byte E4M3 codes (rows of 128 bytes, pieces of 8 channels = 8 bytes); they are widened
@@ -442,26 +458,17 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
   constexpr int kDepth = 2;              // block pairs in flight per wavefront
   constexpr int kKeyLoads = FP8 ? 2 : 4; // 16-byte loads per key row and lane
   using Piece = std::conditional_t<FP8, u32x2, u32x4>;
+  __shared__ float sm_ml[WAVES][G][2];
+  __shared__ float sm_o[WAVES][G][D];
   const int Hkv = Hq / group;
-  const int g = blockIdx.x % Hkv;  // kv head fastest: workgroups go round-robin to the XCDs
-  int s = blockIdx.x / Hkv, part = 0;  // no context is split: one item per sequence
-  if (num_parts > 1) {
-    if (lpt_order) {
-      decode_work_item(context_lens, num_seqs, partition, max_blocks * kBlock, blockIdx.x / Hkv, s, part);
-    } else {
-      const int rank = blockIdx.x / Hkv;
-      s = rank % num_seqs;
-      part = rank / num_seqs;
-      if (part * partition >= capped(context_lens[s], max_blocks * kBlock) && part != 0) s = -1;
-    }
-  }
-  if (s < 0) return;
-  const int n = capped(context_lens[s], max_blocks * kBlock);
-  const int start = part * partition;
-  const int end = min(n, start + partition);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = lane & 15, hq = lane >> 4;
 
+  // One piece of work: keys [start, end) of sequence s (n cached tokens) for kv head g.  The result goes to O when
+  // ws_base < 0 (the piece is the whole context), else the partial (m, l, o) of query head j of the group goes to
+  // entry ws_base + j * ws_stride of the workspace.
+  auto piece = [&](const int s, const int g, const int start, const int end, const int64_t ws_base,
+                   const int64_t ws_stride) {
   bf16x8 qop[4];
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
@@ -591,8 +598,6 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
   l += __shfl_xor(l, 32);
 
   // merge the wavefronts through LDS; lane (q, hq) owns channels 32*hq + 8*v + i of query q
-  __shared__ float sm_ml[WAVES][G][2];
-  __shared__ float sm_o[WAVES][G][D];
   if (c < group) {
     if (hq == 0) {
       sm_ml[wave][c][0] = m;
@@ -617,11 +622,11 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
       lt += sm_ml[w][j][1] * a;
       ot += sm_o[w][j][col] * a;
     }
-    const int64_t row = (int64_t)s * Hq + g * group + j;
-    if (num_parts == 1) {
+    if (ws_base < 0) {
+      const int64_t row = (int64_t)s * Hq + g * group + j;
       Elem<uint16_t>::store(O + row * D + col, lt > 0.f ? ot / lt * out_scale : 0.f);
     } else {
-      const int64_t p = row * num_parts + part;
+      const int64_t p = ws_base + j * ws_stride;
       ws.o[p * D + col] = ot;
       if (col == 0) {
         ws.ml[p * 2] = mn;
@@ -629,6 +634,157 @@ paged_decode_mfma_kernel(const uint16_t *__restrict__ Q, uint16_t *__restrict__ 
       }
     }
   }
+  };  // piece
+
+  if (order == kOrderEven) {
+    // Even split.  The (sequence, kv head) rows of the launch, sequence-major, form one line on which a row takes its
+    // key pairs (32 keys each) plus kRowCost units in front of them (what starting and finishing a piece costs a
+    // workgroup, in pairs' worth of streaming); workgroup w takes the units [w * C, (w + 1) * C) of the line,
+    // C = ceil(total / workgroups): every workgroup gets the same amount of work, whatever the mix of context
+    // lengths, and a row cut by a workgroup boundary gets one partial result per workgroup that holds some of its
+    // pairs.  Partial (row r, workgroup w) lives in workspace entry r + w: along the line either r or w or both
+    // grow from one piece to the next, so the entries are distinct, rows + workgroups in all.
+    __shared__ int sm_cost[kMaxEvenSeqs], sm_before[kMaxEvenSeqs + 1], sm_tokens[kMaxEvenSeqs];
+    for (int i = threadIdx.x; i < num_seqs; i += WAVES * 64) {
+      const int t = capped(context_lens[i], max_blocks * kBlock);
+      sm_tokens[i] = t;
+      sm_cost[i] = even_row_cost(t);
+    }
+    __syncthreads();
+    if (wave == 0) {  // running sum of the sequences' costs, 64 sequences at a time
+      int carry = 0;
+      for (int i0 = 0; i0 < num_seqs; i0 += 64) {
+        const int v = i0 + lane < num_seqs ? sm_cost[i0 + lane] : 0;
+        int incl = v;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+          const int up = __shfl_up(incl, d);
+          if (lane >= d) incl += up;
+        }
+        if (i0 + lane < num_seqs) sm_before[i0 + lane] = carry + incl - v;
+        carry += __shfl(incl, 63);
+      }
+      if (lane == 0) sm_before[num_seqs] = carry;
+    }
+    __syncthreads();
+    const int total = Hkv * sm_before[num_seqs];
+    const int per_wg = (total + (int)gridDim.x - 1) / (int)gridDim.x;
+    int x = (int)blockIdx.x * per_wg;
+    const int x_end = min(x + per_wg, total);
+    if (x >= x_end) return;
+    int lo = 0, hi = num_seqs;  // the last sequence whose first unit is not behind x (it is not empty: x < total)
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (Hkv * sm_before[mid] <= x) lo = mid; else hi = mid;
+    }
+    int s = lo;
+    while (x < x_end) {
+      const int cost = sm_cost[s], off = x - Hkv * sm_before[s];
+      const int g = off / cost, at = off - g * cost;
+      const int take = min(cost - at, x_end - x);
+      const int first = max(at - kRowCost, 0), last = max(at + take - kRowCost, 0);  // the pairs among these units
+      if (last > first) {
+        piece(s, g, first * 2 * kBlock, min(sm_tokens[s], last * 2 * kBlock), ((int64_t)s * Hkv + g + blockIdx.x) * group, 1);
+        __syncthreads();  // the merge buffers are used again by the next piece
+      }
+      x += take;
+      if (at + take == cost && g == Hkv - 1) {
+        do ++s; while (s < num_seqs && sm_cost[s] == 0);
+      }
+    }
+    return;
+  }
+  const int g = blockIdx.x % Hkv;  // kv head fastest: workgroups go round-robin to the XCDs
+  int s = blockIdx.x / Hkv, part = 0;  // no context is split: one item per sequence
+  if (num_parts > 1) {
+    if (order == kOrderLongest) {
+      decode_work_item(context_lens, num_seqs, partition, max_blocks * kBlock, blockIdx.x / Hkv, s, part);
+    } else {
+      const int rank = blockIdx.x / Hkv;
+      s = rank % num_seqs;
+      part = rank / num_seqs;
+      if (part * partition >= capped(context_lens[s], max_blocks * kBlock) && part != 0) s = -1;
+    }
+  }
+  if (s < 0) return;
+  const int n = capped(context_lens[s], max_blocks * kBlock);
+  const int start = part * partition;
+  piece(s, g, start, min(n, start + partition), num_parts == 1 ? -1 : ((int64_t)s * Hq + g * group) * num_parts + part,
+        num_parts);
+}
+
+// The merge of an evenly split launch (kOrderEven): one workgroup per (sequence, q head) finds the workgroups of the
+// first kernel that touched its row, from the same running sums, and merges their partial results.
+template <typename T, int D>
+__global__ void __launch_bounds__(D)
+decode_combine_even_kernel(T *__restrict__ O, const int32_t *__restrict__ context_lens, int cap, int Hq, int group,
+                           int num_seqs, int num_wgs, float out_scale, Workspace ws) {
+  constexpr int kWaves = D / 64;
+  const int s = blockIdx.x / Hq, h = blockIdx.x % Hq, col = threadIdx.x;
+  const int Hkv = Hq / group, g = h / group, j = h % group;
+  __shared__ int sm_int[3][kWaves];
+  __shared__ float sm_red[2][kWaves];
+  __shared__ float sm_weight[1024];  // per piece: exp(m_w - m); the host launches at most this many workgroups
+  int before = 0, all = 0, mine = 0;
+  for (int i = threadIdx.x; i < num_seqs; i += D) {
+    const int cost = even_row_cost(capped(context_lens[i], cap));
+    all += cost;
+    if (i < s) before += cost;
+    if (i == s) mine = cost;
+  }
+#pragma unroll
+  for (int d = 32; d > 0; d >>= 1) {
+    before += __shfl_xor(before, d);
+    all += __shfl_xor(all, d);
+    mine += __shfl_xor(mine, d);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    sm_int[0][threadIdx.x >> 6] = before;
+    sm_int[1][threadIdx.x >> 6] = all;
+    sm_int[2][threadIdx.x >> 6] = mine;
+  }
+  __syncthreads();
+  before = all = mine = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    before += sm_int[0][w];
+    all += sm_int[1][w];
+    mine += sm_int[2][w];
+  }
+  float lt = 0.f, ot = 0.f;
+  if (mine > 0) {  // uniform over the workgroup
+    const int total = Hkv * all, per_wg = (total + num_wgs - 1) / num_wgs;
+    const int x0 = Hkv * before + g * mine + kRowCost;             // the row's first pair on the line
+    const int w_first = x0 / per_wg, pieces = (x0 + mine - kRowCost - 1) / per_wg - w_first + 1;
+    const int64_t base = ((int64_t)s * Hkv + g + w_first) * group + j;
+    // the pieces' maxima and sums side by side (one piece per thread and round), then their weights
+    float mn = -INFINITY;
+    for (int w = threadIdx.x; w < pieces; w += D) mn = fmaxf(mn, ws.ml[(base + (int64_t)w * group) * 2]);
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) mn = fmaxf(mn, __shfl_xor(mn, d));
+    if ((threadIdx.x & 63) == 0) sm_red[0][threadIdx.x >> 6] = mn;
+    __syncthreads();
+    mn = sm_red[0][0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) mn = fmaxf(mn, sm_red[0][w]);
+    const float ms = safe_max(mn);
+    for (int w = threadIdx.x; w < pieces; w += D) {
+      const int64_t i = base + (int64_t)w * group;
+      const float a = fexp<T>(ws.ml[i * 2] - ms);
+      sm_weight[w] = a;
+      lt += ws.ml[i * 2 + 1] * a;
+    }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) lt += __shfl_xor(lt, d);
+    if ((threadIdx.x & 63) == 0) sm_red[1][threadIdx.x >> 6] = lt;
+    __syncthreads();
+    lt = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) lt += sm_red[1][w];
+#pragma unroll 8
+    for (int w = 0; w < pieces; ++w) ot += ws.o[(base + (int64_t)w * group) * D + col] * sm_weight[w];
+  }
+  Elem<T>::store(O + (int64_t)blockIdx.x * D + col, lt > 0.f ? ot / lt * out_scale : 0.f);
 }
 
 // One workgroup per (sequence, q head): merges the partitions that the context spans.
@@ -662,12 +818,14 @@ struct Plan {
   int partition, num_parts, waves;
   bool mfma;
   bool lpt;  // workgroups take the launch's (sequence, partition) items longest first (see decode_work_item)
+  // even split (kOrderEven): even_wgs workgroups share the launch's key pairs equally; 0 = not used
+  int even_wgs;
 };
 
 Plan make_plan(const lkv_ctx *c, int num_seqs, int max_blocks) {
   const int64_t tokens = (int64_t)max_blocks * kBlock;
   const int64_t units = (int64_t)num_seqs * c->cfg.num_kv_heads;
-  Plan p{0, 1, 4, false, false};
+  Plan p{0, 1, 4, false, false, 0};
   p.mfma = (c->cfg.dtype == LKV_BF16 || c->cfg.dtype == LKV_FP8_E4M3) && c->cfg.head_dim == 128;
   if (p.mfma) {
     // Measured on MI355X (sweep of partition 256..4096 x 2/4/8 wavefronts over batches of 1..256 sequences, contexts
@@ -694,6 +852,20 @@ Plan make_plan(const lkv_ctx *c, int num_seqs, int max_blocks) {
   static int cus = 0;
   if (cus == 0 && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess) cus = 256;
   p.lpt = p.mfma && num_seqs <= 256 && units * p.num_parts <= (int64_t)8 * cus;
+  // A split launch with FEW rows (sequences x kv heads) ends when its largest item ends, and its partitions have to
+  // be small to give every CU something, which multiplies the per-workgroup start-up and the merge work.  Such
+  // launches are cut evenly instead: one workgroup per CU, every one with the same share of the launch's key pairs
+  // (kOrderEven).  Measured on MI355X, partitioned -> even: one 16384-token context of the 70B shape 31 -> 26 us, of
+  // the 7B shape 71 -> 57 us, four 8192-token contexts of the 70B shape 42 -> 35 us.  From about half a row per CU
+  // on, the partitioned launch with its dynamic order is as good or better (16 ragged contexts x 8 kv heads: 87.5
+  // against 90 us; 4 x 16385 tokens x 32 heads: 195 either way): equal shares end with the slowest CU, while
+  // workgroups handed out as CUs become free even out the CUs' unequal rates.  A partition size set by the caller
+  // keeps the partitioned launch.
+  if (p.lpt && p.num_parts > 1 && c->cfg.decode_partition == 0 && num_seqs <= kMaxEvenSeqs && units * 8 <= (int64_t)cus * 3 &&
+      units * (tokens / (2 * kBlock) + 1 + kRowCost) < ((int64_t)1 << 30)) {
+    p.even_wgs = cus < 1024 ? cus : 1024;  // the merge kernel keeps one weight per workgroup in LDS
+    p.waves = 8;
+  }
   return p;
 }
 
@@ -709,14 +881,15 @@ hipError_t launch_w(const lkv_ctx *c, const Plan &p, const void *Q, void *O, con
 template <int G, int WAVES, bool FP8>
 hipError_t launch_mfma(const lkv_ctx *c, const Plan &p, const void *Q, void *O, const int32_t *bt, int max_blocks,
                        const int32_t *cl, int num_seqs, Workspace ws, hipStream_t s) {
-  // one-dimensional grid, kv head fastest, then the rank of the (sequence, partition) work item
+  // one-dimensional grid: the even split's workgroups, or kv head fastest, then the rank of the (sequence,
+  // partition) work item
   if ((int64_t)c->cfg.num_kv_heads * num_seqs * p.num_parts > INT32_MAX) return hipErrorInvalidValue;
-  dim3 grid((unsigned)(c->cfg.num_kv_heads * num_seqs * p.num_parts)), block(WAVES * 64);
-  const int lpt = p.lpt ? 1 : 0;
+  dim3 grid((unsigned)(p.even_wgs ? p.even_wgs : c->cfg.num_kv_heads * num_seqs * p.num_parts)), block(WAVES * 64);
+  const int order = p.even_wgs ? kOrderEven : p.lpt ? kOrderLongest : kOrderPlain;
   launch_timed(c, true, p.num_parts == 1, paged_decode_mfma_kernel<G, WAVES, FP8>, grid, block, s, (const uint16_t *)Q,
                      (uint16_t *)O, c->pool, bt, max_blocks, cl, c->cfg.num_q_heads,
                      c->cfg.num_q_heads / c->cfg.num_kv_heads, c->block_bytes, (int)c->cfg.num_pool_blocks, FP8 ? c->scale * c->k_scale : c->scale, FP8 ? c->v_scale : 1.f,
-                     p.partition, p.num_parts, num_seqs, lpt, ws);
+                     p.partition, p.num_parts, num_seqs, order, ws);
   return hipGetLastError();
 }
 
@@ -726,7 +899,9 @@ hipError_t launch_t(const lkv_ctx *c, const void *Q, void *O, const int32_t *bt,
   const Plan p = make_plan(c, num_seqs, max_blocks);
   if (num_seqs > 65535 || p.num_parts > 65535) return hipErrorInvalidValue;  // grid y and z limits
   const int Hq = c->cfg.num_q_heads;
-  Workspace ws{wsbuf, wsbuf + (int64_t)num_seqs * Hq * p.num_parts * 2};
+  const int64_t entries = p.even_wgs ? ((int64_t)num_seqs * c->cfg.num_kv_heads + p.even_wgs) * (Hq / c->cfg.num_kv_heads)
+                                     : (int64_t)num_seqs * Hq * p.num_parts;
+  Workspace ws{wsbuf, wsbuf + entries * 2};
   hipError_t e;
   const bool fp8 = c->cfg.dtype == LKV_FP8_E4M3;
   if (p.mfma && sizeof(T) == 2 && D == 128) {  // make_plan sets mfma only for this case
@@ -744,6 +919,11 @@ hipError_t launch_t(const lkv_ctx *c, const void *Q, void *O, const int32_t *bt,
     return hipErrorInvalidValue;  // more than 8 heads per kv head only on the matrix-core kernel
   }
   if (e != hipSuccess || p.num_parts == 1) return e;
+  if (p.even_wgs) {
+    launch_timed(c, false, true, decode_combine_even_kernel<T, D>, dim3(num_seqs * Hq), dim3(D), s, (T *)O, cl,
+                 max_blocks * kBlock, Hq, Hq / c->cfg.num_kv_heads, num_seqs, p.even_wgs, fp8 ? c->v_scale : 1.f, ws);
+    return hipGetLastError();
+  }
   launch_timed(c, false, true, decode_combine_kernel<T, D>, dim3(num_seqs * Hq), dim3(D), s, (T *)O, cl, max_blocks * kBlock, Hq,
                      p.partition,
                      p.num_parts, fp8 ? c->v_scale : 1.f, ws);
@@ -776,9 +956,12 @@ bool decode_supported(const lkv_ctx *c) {
 }
 
 int64_t decode_workspace_bytes(const lkv_ctx *c, int32_t num_seqs, int32_t max_blocks) {
-  const int64_t parts = make_plan(c, num_seqs, max_blocks).num_parts;
-  if (parts <= 1) return 0;
-  return (int64_t)num_seqs * c->cfg.num_q_heads * parts * (2 + c->cfg.head_dim) * (int64_t)sizeof(float);
+  const Plan p = make_plan(c, num_seqs, max_blocks);
+  if (p.num_parts <= 1) return 0;
+  const int64_t group = c->cfg.num_q_heads / c->cfg.num_kv_heads;
+  const int64_t entries = p.even_wgs ? ((int64_t)num_seqs * c->cfg.num_kv_heads + p.even_wgs) * group
+                                     : (int64_t)num_seqs * c->cfg.num_q_heads * p.num_parts;
+  return entries * (2 + c->cfg.head_dim) * (int64_t)sizeof(float);
 }
 
 hipError_t launch_paged_decode(const lkv_ctx *c, const void *Q, void *O, const int32_t *bt, int32_t max_blocks,

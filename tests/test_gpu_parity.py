@@ -322,6 +322,34 @@ def test_decode_ragged_batches_longest_first_work_list(B, Hq, Hkv, max_len):
     sc.close()
 
 
+@pytest.mark.parametrize("Hq,Hkv,lens", [(8, 8, (5000, 31, 640, 700, 33, 4097, 1)), (64, 8, (16384, 100)),
+                                         (32, 2, (900, 2000, 17)), (4, 1, (9000,))])
+def test_decode_even_split_of_launches_with_few_rows(Hq, Hkv, lens):
+    """A split launch with few (sequence, kv head) rows is cut into equal shares of key pairs, one per CU, whatever
+    rows they belong to: rows cut by several workgroups, workgroups that hold several short rows, rows that end on
+    a pair boundary or in the middle of a block, one to sixteen query heads per kv head.  Then the same launch with
+    contexts cut to zero, to one token and to a block boundary (the shares move, empty rows give zero rows)."""
+    shape = wl.KVShape(1, Hq, Hkv, 128, 16, "bf16")
+    sc = Scenario(23, shape, lens, sum((n + 16) // 16 + 1 for n in lens) + 8)
+    sc.prefill_layer(0, check_attn=False)
+    sc.decode_step(0)
+    B = len(lens)
+    q, _, _ = wl.decode_qkv(23, 0, 5, B, shape, 1.0, q_gain=3.0)
+    bt = sc.c.padded_block_table(range(B), 0)
+    ctx = np.asarray([n + 1 for n in lens], dtype=np.int32)
+    ctx[0] = 0
+    if B > 3:
+        ctx[2], ctx[3], ctx[-1] = 1, 512, 0
+    Od = H.empty_like_storage(q.shape, "bf16")
+    Od.fill_(0x7FC0)
+    sc.c.paged_decode_attention(0, H.to_dev(q), Od, H.to_dev(bt), bt.shape[1], H.to_dev(ctx), B)
+    got = H.to_host(Od, "bf16")
+    ref = sc.o.paged_decode_attention(q, bt, ctx, threads=ORC_THREADS)
+    assert (got[0] == 0).all()
+    H.check_attention(got, ref, "bf16", 1.0, "even split, contexts cut")
+    sc.close()
+
+
 @pytest.mark.parametrize("Hq,Hkv,lens", [(8, 2, (3000, 1111)), (8, 1, (2500,)), (4, 4, (600, 90, 1))])
 def test_decode_small_batches_get_smaller_partitions_from_the_plan(Hq, Hkv, lens):
     """With the library's own plan (no partition given) a launch of a few sequences is cut into partitions of as
