@@ -349,6 +349,19 @@ lkv_status lkv_paged_decode_attention(lkv_ctx *ctx, int32_t layer, const void *Q
  * waits for the device (earlier launches may still use the old one), frees it and allocates the new one. */
 lkv_status lkv_reserve_decode_workspace(lkv_ctx *ctx, int32_t num_seqs, int32_t max_blocks_per_seq);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): the same operation, arguments, kernels and results as lkv_paged_decode_attention, with the
+ * split-K partial results in a fixed array that is part of the library's device code (8 MiB per GPU, held until the
+ * process ends) instead of the context's workspace.  Calls no hipMalloc / hipFree and creates nothing.  A call whose
+ * partial results exceed the array (num_seqs * num_q_heads * partitions * (head_dim + 2) * 4 bytes > 8 MiB) returns
+ * LKV_ERR_INVALID_ARG and enqueues nothing.  Kernel profiling (lkv_set_profiling) does not cover this call.  Every
+ * call on a GPU, from any context, uses that GPU's one array: calls that overlap in time on one GPU (two streams
+ * without an event between them) race on it; each call overwrites what it reads, so nothing needs clearing between
+ * calls. */
+lkv_status lkv_paged_decode_attention_static(lkv_ctx *ctx, int32_t layer, const void *Q, void *O,
+                                             const int32_t *block_table, int32_t max_blocks_per_seq,
+                                             const int32_t *context_lens, int32_t num_seqs, void *stream);
+
 /* ------------------------------------------------------------------ ordering and statistics */
 /* Makes `stream` wait for the last recorded event `ev` of `layer` (no-op if never recorded). */
 lkv_status lkv_stream_wait_event(lkv_ctx *ctx, int32_t layer, int32_t ev, void *stream);

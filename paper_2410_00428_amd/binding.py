@@ -35,7 +35,7 @@ EXPORTS = (
     "lkv_host_tier_config", "lkv_offload_layer_pageable", "lkv_reload_layer_pageable", "lkv_host_tier_synchronize",
     "lkv_set_link_gate",
     "lkv_stream_wait_event", "lkv_event_synchronize", "lkv_set_profiling", "lkv_get_stats",
-    "lkv_reserve_decode_workspace",
+    "lkv_reserve_decode_workspace", "lkv_paged_decode_attention_static",
     "lkv_prefill_time", "lkv_offload_time", "lkv_plan_offload", "lkv_allow_prefill_time", "lkv_max_prefills",
     "lkv_forecast_avail", "lkv_pressure_offload",
 )
@@ -133,6 +133,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "lkv_set_profiling": (i32, [vp, i32]),
         "lkv_get_stats": (i32, [vp, P(LkvStats), i64]),
         "lkv_reserve_decode_workspace": (i32, [vp, i32, i32]),
+        "lkv_paged_decode_attention_static": (i32, [vp, i32, vp, vp, vp, i32, vp, i32, vp]),
         "lkv_prefill_time": (ctypes.c_double, [P(CostModel), i64]),
         "lkv_offload_time": (ctypes.c_double, [P(CostModel), i64, i32]),
         "lkv_plan_offload": (i32, [P(CostModel), i64, P(i32), vp]),
@@ -395,6 +396,12 @@ class LKV:
 
     def set_profiling(self, on: bool) -> None:
         self._check(self.lib.lkv_set_profiling(self.h, int(bool(on))))
+
+    def paged_decode_attention_static(self, layer: int, Q, O, block_table, max_blocks_per_seq: int, context_lens,
+                                      num_seqs: int, stream=None) -> None:
+        self._check(self.lib.lkv_paged_decode_attention_static(self.h, layer, _ptr(Q), _ptr(O), _ptr(block_table),
+                                                               max_blocks_per_seq, _ptr(context_lens), num_seqs,
+                                                               _stream(stream)))
 
     def reserve_decode_workspace(self, num_seqs: int, max_blocks_per_seq: int) -> None:
         self._check(self.lib.lkv_reserve_decode_workspace(self.h, num_seqs, max_blocks_per_seq))

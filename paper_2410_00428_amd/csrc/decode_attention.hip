@@ -13,7 +13,13 @@
 // exp(m_i - m) weights.
 
 #include "lkv_internal.hpp"
+#include <mutex>
 #include <type_traits>
+
+// Split-K partial results for callers that cannot allocate device memory (lkv_paged_decode_attention_static): a fixed
+// array in the library's device image, one copy per GPU at that GPU's own address.  In host code the name `scratch`
+// is only a handle for hipGetSymbolAddress; the kernels get the address that call returns, like any other buffer.
+static __device__ __align__(256) unsigned char scratch[LKV_STATIC_DECODE_SCRATCH_BYTES];
 
 namespace {
 
@@ -945,6 +951,29 @@ hipError_t launch_g(const lkv_ctx *c, const void *Q, void *O, const int32_t *bt,
 }  // namespace
 
 namespace lkv {
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float *g_scratch_ptr[kMaxDevices] = {};
+}  // namespace
+
+hipError_t static_scratch_init(int device) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[device]) return hipSuccess;
+  void *p = nullptr;
+  const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));  // of the CURRENT device's copy
+  if (e != hipSuccess) return e;
+  g_scratch_ptr[device] = (float *)p;
+  return hipSuccess;
+}
+
+float *static_scratch(int device) {
+  if (device < 0 || device >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  return g_scratch_ptr[device];
+}
 
 bool decode_supported(const lkv_ctx *c) {
   const int g = c->cfg.num_q_heads / c->cfg.num_kv_heads;

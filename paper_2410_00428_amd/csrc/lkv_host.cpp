@@ -352,6 +352,11 @@ static lkv_status create_impl(const lkv_config *cfg, lkv_ctx **out, bool with_de
     c->err = std::string("hipGetDevice failed: ") + hipGetErrorString(e);
     return bail(LKV_ERR_DEVICE);
   }
+  e = lkv::static_scratch_init(c->device);  // address of this device's fixed decode scratch, looked up once
+  if (e != hipSuccess) {
+    c->err = std::string("hipGetSymbolAddress of the fixed decode scratch failed: ") + hipGetErrorString(e);
+    return bail(LKV_ERR_DEVICE);
+  }
   if (cfg->pool) {
     c->pool = (char *)cfg->pool;
   } else {
@@ -872,6 +877,38 @@ lkv_status lkv_paged_decode_attention(lkv_ctx *c, int32_t layer, const void *Q, 
   if (lkv_status st = timed_begin(c, s, &t0)) return st;
   LKV_HIP(c, lkv::launch_paged_decode(c, Q, O, block_table, max_blocks_per_seq, context_lens, num_seqs, c->ws, s));
   if (lkv_status st = timed_end(c, s, t0, 0, lkv_ctx::kTimedDecode)) return st;
+  c->stats.decode_calls += 1;
+  return LKV_OK;
+}
+
+lkv_status lkv_paged_decode_attention_static(lkv_ctx *c, int32_t layer, const void *Q, void *O,
+                                             const int32_t *block_table, int32_t max_blocks_per_seq,
+                                             const int32_t *context_lens, int32_t num_seqs, void *stream) {
+  if (!c) return LKV_ERR_INVALID_ARG;
+  if (c->logical_only) return fail(c, LKV_ERR_DEVICE, "lkv_paged_decode_attention_static: this context has no device resources (lkv_create_logical)");
+  if (bad_layer(c, layer) || num_seqs < 0 || max_blocks_per_seq < 0)
+    return fail(c, LKV_ERR_INVALID_ARG, "lkv_paged_decode_attention_static: bad layer or count");
+  if (!lkv::decode_supported(c))
+    return fail(c, LKV_ERR_UNSUPPORTED,
+                "lkv_paged_decode_attention_static: head_dim %d / block_size %d / dtype %d / %d query heads per kv head is not built",
+                c->cfg.head_dim, c->cfg.block_size, c->cfg.dtype, c->cfg.num_q_heads / c->cfg.num_kv_heads);
+  if (num_seqs == 0) return LKV_OK;
+  if (!Q || !O || !context_lens || (max_blocks_per_seq && !block_table))
+    return fail(c, LKV_ERR_INVALID_ARG, "lkv_paged_decode_attention_static: NULL pointer");
+  if (((uintptr_t)Q | (uintptr_t)O) & 15)
+    return fail(c, LKV_ERR_INVALID_ARG, "lkv_paged_decode_attention_static: Q and O must be 16-byte aligned");
+  const int64_t need = lkv::decode_workspace_bytes(c, num_seqs, max_blocks_per_seq);
+  if (need > (int64_t)LKV_STATIC_DECODE_SCRATCH_BYTES)
+    return fail(c, LKV_ERR_INVALID_ARG,
+                "lkv_paged_decode_attention_static: %d sequences with tables of %d blocks need %lld bytes of split-K "
+                "partial results, the fixed scratch holds %lld",
+                num_seqs, max_blocks_per_seq, (long long)need, (long long)LKV_STATIC_DECODE_SCRATCH_BYTES);
+  float *ws = lkv::static_scratch(c->device);  // the address hipGetSymbolAddress gave at lkv_create, never the symbol
+  if (!ws) return fail(c, LKV_ERR_DEVICE, "lkv_paged_decode_attention_static: the fixed scratch of device %d is unknown", c->device);
+  hipStream_t s = (hipStream_t)stream;
+  if (lkv_status st = wait_event(c, layer, LKV_EV_RELOADED, s)) return st;
+  // no profiling events here: taking one from the free list may create it
+  LKV_HIP(c, lkv::launch_paged_decode(c, Q, O, block_table, max_blocks_per_seq, context_lens, num_seqs, ws, s));
   c->stats.decode_calls += 1;
   return LKV_OK;
 }

@@ -141,6 +141,11 @@ hipError_t launch_paged_decode(const lkv_ctx *c, const void *Q, void *O, const i
                                int32_t max_blocks_per_seq, const int32_t *context_lens, int32_t num_seqs,
                                float *ws, hipStream_t s);
 bool decode_supported(const lkv_ctx *c);
+// The fixed split-K scratch of lkv_paged_decode_attention_static: static_scratch_init looks its address up once per
+// device (that device must be current), static_scratch returns it (nullptr before the lookup).
+#define LKV_STATIC_DECODE_SCRATCH_BYTES (8 << 20)
+hipError_t static_scratch_init(int device);
+float *static_scratch(int device);
 
 hipError_t launch_prefill(const lkv_ctx *c, const void *Q, const void *K, const void *V, void *O,
                           const int32_t *cu_seqlens, int32_t num_seqs, int32_t max_seqlen, int64_t total_tokens,

@@ -48,7 +48,7 @@ def test_device_calls_fail_loudly_on_a_logical_context():
     assert e.value.status == lkv.LKV_ERR_DEVICE
     with pytest.raises(lkv.LkvError):
         c.paged_decode_attention(0, 0, 0, 0, 0, 0, 0)
-    for call in (lambda: c.reserve_decode_workspace(4, 64),):
+    for call in (lambda: c.reserve_decode_workspace(4, 64), lambda: c.paged_decode_attention_static(0, 0, 0, 0, 0, 0, 0)):
         with pytest.raises(lkv.LkvError) as e:
             call()
         assert e.value.status == lkv.LKV_ERR_DEVICE
