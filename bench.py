@@ -432,7 +432,9 @@ def mixed_iteration(args) -> dict:
     out["roofline"]["traffic"] = measured_traffic("paged_decode_mfma_kernel", 5) if args.kv_dtype == "bf16" else None
     if not args.no_extras:
         # the decode batches of the other configurations (the 70B-shaped GQA batch of workload 4 among them)
-        out["decode_other_workloads"] = decode_other_workloads(torch, dev, numbers=(3, 4))
+        out["decode_other_workloads"] = decode_other_workloads(torch, dev, numbers=(3, 4, 5))
+        out["decode_other_workloads"]["note"] = ("each batch's decode launches alone (a few layers in turn, nothing else on "
+                                                 "the GPU); 5 is the main workload's own batch outside the iteration")
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds, lens=sorted(dlens)[len(dlens) // 2 - 1:len(dlens) // 2 + 1])
     return out
