@@ -39,6 +39,9 @@ int main(void) {
   CHECK(lkv_alloc_layer_blocks(c, 7, 4, 16 * 40) == LKV_ERR_NO_BLOCKS); /* 40 blocks do not fit */
   CHECK(lkv_num_free_blocks(c) == 29);
   CHECK(lkv_write_kv(c, 3, NULL, NULL, NULL, 0, NULL) == LKV_ERR_DEVICE); /* no device behind this context */
+  CHECK(lkv_reserve_decode_workspace(c, 4, 64) == LKV_ERR_DEVICE);
+  CHECK(lkv_paged_decode_attention_static(c, 3, NULL, NULL, NULL, 0, NULL, 0, NULL) == LKV_ERR_DEVICE);
+  CHECK(LKV_RES_IN_FLIGHT == 3);                                        /* never reported without a device */
   CHECK(strlen(lkv_last_error(c)) > 0);
   CHECK(lkv_free_layer_blocks(c, 7, 3, 1) == LKV_OK);
   CHECK(lkv_layer_residency(c, 7, 3, &res) == LKV_OK && res == LKV_RES_HOST);

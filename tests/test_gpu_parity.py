@@ -322,12 +322,16 @@ def test_decode_ragged_batches_longest_first_work_list(B, Hq, Hkv, max_len):
     sc.close()
 
 
+MANY_SHORT = tuple(int(x) for x in np.random.default_rng(77).integers(1, 400, size=89)) + (5000,)
+
+
 @pytest.mark.parametrize("Hq,Hkv,lens", [(8, 8, (5000, 31, 640, 700, 33, 4097, 1)), (64, 8, (16384, 100)),
-                                         (32, 2, (900, 2000, 17)), (4, 1, (9000,))])
+                                         (32, 2, (900, 2000, 17)), (4, 1, (9000,)), (4, 1, MANY_SHORT)])
 def test_decode_even_split_of_launches_with_few_rows(Hq, Hkv, lens):
     """A split launch with few (sequence, kv head) rows is cut into equal shares of key pairs, one per CU, whatever
     rows they belong to: rows cut by several workgroups, workgroups that hold several short rows, rows that end on
-    a pair boundary or in the middle of a block, one to sixteen query heads per kv head.  Then the same launch with
+    a pair boundary or in the middle of a block, one to sixteen query heads per kv head, ninety sequences (the
+    running sums take two rounds of 64).  Then the same launch with
     contexts cut to zero, to one token and to a block boundary (the shares move, empty rows give zero rows)."""
     shape = wl.KVShape(1, Hq, Hkv, 128, 16, "bf16")
     sc = Scenario(23, shape, lens, sum((n + 16) // 16 + 1 for n in lens) + 8)
