@@ -270,10 +270,13 @@ lkv_status lkv_prefill_attention(lkv_ctx *ctx, int32_t layer, const void *Q, con
                                  void *O, const int32_t *cu_seqlens, int32_t num_seqs,
                                  int32_t max_seqlen, int64_t total_tokens, int32_t causal, void *stream);
 
-/* Offload image of one layer (Sections 3.2.1, 4): waits (on `stream`) for LKV_EV_KV_WRITTEN of
- * the layer, gathers blocks block_ids[0..n) (host array) into device staging and copies them to
- * pinned_dst (n*beta bytes), all on `stream`; records LKV_EV_PACKED after the last gather and
- * LKV_EV_OFFLOADED after the last copy.  Does not touch tables or the free list.  Host-link copies are paced:
+/* Offload image of one layer (Sections 3.2.1, 4): gathers blocks block_ids[0..n) (host array) into device staging
+ * and copies them to pinned_dst (n*beta bytes).  The copies run on `stream`; the gathers run on a helper stream of
+ * the library, behind everything `stream` holds when the call is made and behind LKV_EV_KV_WRITTEN of the layer, into
+ * two staging buffers in turn, so that the gather of one chunk (or of the next layer's call) overlaps the copy of the
+ * one before it and the link stays busy back to back.  Records LKV_EV_PACKED after the last gather (on the helper
+ * stream) and LKV_EV_OFFLOADED after the last copy (on `stream`): work put on `stream` after the call is ordered
+ * behind the whole offload.  Does not touch tables or the free list.  Host-link copies are paced:
  * at most two per direction are queued at a time, so this call (and lkv_unpack_layer_blocks) blocks the calling
  * thread until the copy two places ahead of its own has finished (at most the duration of one chunk's copy per
  * chunk issued; staging_bytes sets the chunk size). */

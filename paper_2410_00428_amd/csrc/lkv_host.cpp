@@ -57,8 +57,13 @@ lkv_status wait_event(lkv_ctx *c, int32_t layer, int32_t ev, hipStream_t s) {
 
 bool bad_layer(const lkv_ctx *c, int32_t layer) { return layer < 0 || layer >= c->cfg.num_layers; }
 
-lkv_status staging_create(lkv_ctx *c, lkv::Staging &st) {
+lkv_status staging_create(lkv_ctx *c, lkv::Staging &st, bool twin) {
   LKV_HIP(c, hipMalloc((void **)&st.buf, (size_t)(c->staging_blocks * c->block_bytes)));
+  if (twin) {
+    LKV_HIP(c, hipMalloc((void **)&st.buf2, (size_t)(c->staging_blocks * c->block_bytes)));
+    for (auto &e : st.twin_gathered) LKV_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    for (auto &e : st.twin_copied) LKV_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+  }
   size_t ids_bytes = sizeof(int32_t) * (size_t)c->staging_blocks * lkv::Staging::kSlots;
   LKV_HIP(c, hipMalloc((void **)&st.ids_dev, ids_bytes));
   LKV_HIP(c, hipHostMalloc((void **)&st.ids_pinned, ids_bytes, hipHostMallocDefault));
@@ -73,6 +78,11 @@ lkv_status staging_create(lkv_ctx *c, lkv::Staging &st) {
 
 void staging_destroy(lkv::Staging &st) {
   if (st.buf) (void)hipFree(st.buf);
+  if (st.buf2) (void)hipFree(st.buf2);
+  for (auto &e : st.twin_gathered)
+    if (e) (void)hipEventDestroy(e);
+  for (auto &e : st.twin_copied)
+    if (e) (void)hipEventDestroy(e);
   if (st.ids_dev) (void)hipFree(st.ids_dev);
   if (st.ids_pinned) (void)hipHostFree(st.ids_pinned);
   for (auto &e : st.slot_done)
@@ -368,8 +378,8 @@ static lkv_status create_impl(const lkv_config *cfg, lkv_ctx **out, bool with_de
     }
     c->owns_pool = true;
   }
-  lkv_status st = staging_create(c, c->d2h);
-  if (st == LKV_OK) st = staging_create(c, c->h2d);
+  lkv_status st = staging_create(c, c->d2h, true);
+  if (st == LKV_OK) st = staging_create(c, c->h2d, false);
   if (st != LKV_OK) return bail(st);
   c->events.assign((size_t)cfg->num_layers * 4, nullptr);
   c->event_recorded.assign((size_t)cfg->num_layers * 4, 0);
@@ -633,30 +643,45 @@ lkv_status lkv_pack_layer_blocks(lkv_ctx *c, int32_t layer, const int32_t *block
     return fail(c, LKV_ERR_INVALID_ARG, "lkv_pack_layer_blocks: bad argument");
   if (lkv_status st = check_ids(c, block_ids, n)) return st;
   hipStream_t s = (hipStream_t)stream;
-  if (lkv_status st = wait_event(c, layer, LKV_EV_KV_WRITTEN, s)) return st;
   lkv::Staging &sg = c->d2h;
+  // The gathers run on the helper stream, behind everything the caller's stream holds at this point, behind the
+  // layer's write and (after a pageable transfer) behind the last user of the staging memory; the link copies run
+  // on the caller's stream, each behind its gather.  Two staging buffers alternate from chunk to chunk AND from
+  // call to call: the gather of a chunk overlaps the copy of the one before it, so the link is busy back to back.
+  LKV_HIP(c, hipEventRecord(sg.entry, s));
+  LKV_HIP(c, hipStreamWaitEvent(sg.aux, sg.entry, 0));
+  if (lkv_status st = wait_event(c, layer, LKV_EV_KV_WRITTEN, sg.aux)) return st;
+  if (sg.last_user == 2 && sg.buf_used) LKV_HIP(c, hipStreamWaitEvent(sg.aux, sg.buf_free, 0));
+  sg.last_user = 1;
   for (int64_t first = 0; first < n; first += c->staging_blocks) {
     int64_t m = n - first < c->staging_blocks ? n - first : c->staging_blocks;
     int slot;
     link_gate(c);
-    if (lkv_status st = stage_ids(c, sg, block_ids + first, m, s, &slot)) return st;
-    if (sg.buf_used) LKV_HIP(c, hipStreamWaitEvent(s, sg.buf_free, 0));
+    const int b = (int)(sg.twin_chunks & 1);
+    char *stage = b ? sg.buf2 : sg.buf;
+    if (lkv_status st = stage_ids(c, sg, block_ids + first, m, sg.aux, &slot)) return st;
+    if (sg.twin_used[b]) LKV_HIP(c, hipStreamWaitEvent(sg.aux, sg.twin_copied[b], 0));  // its last copy has left
     hipEvent_t t0;
-    if (lkv_status st = timed_begin(c, s, &t0)) return st;
-    LKV_HIP(c, lkv::launch_gather_blocks(c, sg.ids_dev + (size_t)slot * c->staging_blocks, m, sg.buf, s));
-    if (lkv_status st = timed_end(c, s, t0, 2 * m * c->block_bytes, lkv_ctx::kTimedPack)) return st;
-    LKV_HIP(c, hipEventRecord(sg.slot_done[slot], s));
+    if (lkv_status st = timed_begin(c, sg.aux, &t0)) return st;
+    LKV_HIP(c, lkv::launch_gather_blocks(c, sg.ids_dev + (size_t)slot * c->staging_blocks, m, stage, sg.aux));
+    if (lkv_status st = timed_end(c, sg.aux, t0, 2 * m * c->block_bytes, lkv_ctx::kTimedPack)) return st;
+    LKV_HIP(c, hipEventRecord(sg.slot_done[slot], sg.aux));
+    LKV_HIP(c, hipEventRecord(sg.twin_gathered[b], sg.aux));
     if (first + m == n)
-      if (lkv_status st = record_event(c, layer, LKV_EV_PACKED, s)) return st;
+      if (lkv_status st = record_event(c, layer, LKV_EV_PACKED, sg.aux)) return st;
+    LKV_HIP(c, hipStreamWaitEvent(s, sg.twin_gathered[b], 0));
     if (lkv_status st = pace_copy(c, sg)) return st;
-    LKV_HIP(c, hipMemcpyAsync((char *)pinned_dst + first * c->block_bytes, sg.buf, (size_t)(m * c->block_bytes),
+    LKV_HIP(c, hipMemcpyAsync((char *)pinned_dst + first * c->block_bytes, stage, (size_t)(m * c->block_bytes),
                               hipMemcpyDeviceToHost, s));
     if (lkv_status st = copy_issued(c, sg, s)) return st;
+    LKV_HIP(c, hipEventRecord(sg.twin_copied[b], s));
+    sg.twin_used[b] = true;
+    sg.twin_chunks += 1;
     LKV_HIP(c, hipEventRecord(sg.buf_free, s));
     sg.buf_used = true;
   }
   if (n == 0)
-    if (lkv_status st = record_event(c, layer, LKV_EV_PACKED, s)) return st;
+    if (lkv_status st = record_event(c, layer, LKV_EV_PACKED, sg.aux)) return st;
   c->stats.pack_calls += 1;
   c->stats.pack_bytes += n * c->block_bytes;
   return record_event(c, layer, LKV_EV_OFFLOADED, s);
@@ -741,6 +766,7 @@ lkv_status lkv_offload_layer_pageable(lkv_ctx *c, int32_t layer, const int32_t *
   LKV_HIP(c, hipEventRecord(sg.entry, s));
   LKV_HIP(c, hipStreamWaitEvent(sg.aux, sg.entry, 0));
   if (sg.buf_used) LKV_HIP(c, hipStreamWaitEvent(sg.aux, sg.buf_free, 0));
+  sg.last_user = 2;
   for (int64_t first = 0; first < n; first += c->unit_blocks) {
     int64_t m = n - first < c->unit_blocks ? n - first : c->unit_blocks;
     link_gate(c);

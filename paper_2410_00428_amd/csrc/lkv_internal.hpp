@@ -59,6 +59,15 @@ struct Staging {
   bool half_used[2] = {false, false};
   int64_t units_issued = 0;               // picks the half
   hipEvent_t unit_copies[kCopyRing] = {}; // not owned: the ring unit events of the last copies, for the pacing
+  // The pinned offload (lkv_pack_layer_blocks) alternates between buf and a second buffer of the same size, so that
+  // the gather of one chunk (on the helper stream) runs while the link copy of the chunk before it is still going:
+  // the link never waits for a gather, however slowly the gather gets CUs next to an attention kernel.
+  char *buf2 = nullptr;
+  hipEvent_t twin_gathered[2] = {};       // gather into buffer b done (helper stream)
+  hipEvent_t twin_copied[2] = {};         // last copy out of buffer b done (caller's stream)
+  bool twin_used[2] = {false, false};
+  int64_t twin_chunks = 0;                // picks the buffer
+  int last_user = 0;                      // 0 nobody yet, 1 the pinned calls, 2 the pageable calls
 };
 
 }  // namespace lkv

@@ -343,7 +343,7 @@ def test_decode_even_split_of_launches_with_few_rows(Hq, Hkv, lens):
     ctx = np.asarray([n + 1 for n in lens], dtype=np.int32)
     ctx[0] = 0
     if B > 3:
-        ctx[2], ctx[3], ctx[-1] = 1, 512, 0
+        ctx[2], ctx[3], ctx[-1] = 1, min(512, lens[3] // 16 * 16), 0   # a block boundary inside the sequence
     Od = H.empty_like_storage(q.shape, "bf16")
     Od.fill_(0x7FC0)
     sc.c.paged_decode_attention(0, H.to_dev(q), Od, H.to_dev(bt), bt.shape[1], H.to_dev(ctx), B)
