@@ -62,7 +62,6 @@ lkv_status staging_create(lkv_ctx *c, lkv::Staging &st, bool twin) {
   if (twin) {
     LKV_HIP(c, hipMalloc((void **)&st.buf2, (size_t)(c->staging_blocks * c->block_bytes)));
     for (auto &e : st.twin_gathered) LKV_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
-    for (auto &e : st.twin_copied) LKV_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
   }
   size_t ids_bytes = sizeof(int32_t) * (size_t)c->staging_blocks * lkv::Staging::kSlots;
   LKV_HIP(c, hipMalloc((void **)&st.ids_dev, ids_bytes));
@@ -80,8 +79,6 @@ void staging_destroy(lkv::Staging &st) {
   if (st.buf) (void)hipFree(st.buf);
   if (st.buf2) (void)hipFree(st.buf2);
   for (auto &e : st.twin_gathered)
-    if (e) (void)hipEventDestroy(e);
-  for (auto &e : st.twin_copied)
     if (e) (void)hipEventDestroy(e);
   if (st.ids_dev) (void)hipFree(st.ids_dev);
   if (st.ids_pinned) (void)hipHostFree(st.ids_pinned);
@@ -673,11 +670,13 @@ lkv_status lkv_pack_layer_blocks(lkv_ctx *c, int32_t layer, const int32_t *block
     if (lkv_status st = pace_copy(c, sg)) return st;
     LKV_HIP(c, hipMemcpyAsync((char *)pinned_dst + first * c->block_bytes, stage, (size_t)(m * c->block_bytes),
                               hipMemcpyDeviceToHost, s));
+    // one event record between two copies, no more (every packet between them costs link time): the pacing's
+    // event of this copy also tells when the buffer may be gathered into again and when the staging memory is free
+    sg.twin_copied[b] = sg.copy_done[sg.copies_issued % lkv::Staging::kCopyRing];
     if (lkv_status st = copy_issued(c, sg, s)) return st;
-    LKV_HIP(c, hipEventRecord(sg.twin_copied[b], s));
+    sg.pack_last = sg.twin_copied[b];
     sg.twin_used[b] = true;
     sg.twin_chunks += 1;
-    LKV_HIP(c, hipEventRecord(sg.buf_free, s));
     sg.buf_used = true;
   }
   if (n == 0)
@@ -765,7 +764,7 @@ lkv_status lkv_offload_layer_pageable(lkv_ctx *c, int32_t layer, const int32_t *
   // last user of the staging buffer
   LKV_HIP(c, hipEventRecord(sg.entry, s));
   LKV_HIP(c, hipStreamWaitEvent(sg.aux, sg.entry, 0));
-  if (sg.buf_used) LKV_HIP(c, hipStreamWaitEvent(sg.aux, sg.buf_free, 0));
+  if (sg.buf_used) LKV_HIP(c, hipStreamWaitEvent(sg.aux, sg.last_user == 1 ? sg.pack_last : sg.buf_free, 0));
   sg.last_user = 2;
   for (int64_t first = 0; first < n; first += c->unit_blocks) {
     int64_t m = n - first < c->unit_blocks ? n - first : c->unit_blocks;

@@ -64,7 +64,8 @@ struct Staging {
   // the link never waits for a gather, however slowly the gather gets CUs next to an attention kernel.
   char *buf2 = nullptr;
   hipEvent_t twin_gathered[2] = {};       // gather into buffer b done (helper stream)
-  hipEvent_t twin_copied[2] = {};         // last copy out of buffer b done (caller's stream)
+  hipEvent_t twin_copied[2] = {};         // not owned: the pacing event of the last copy out of buffer b
+  hipEvent_t pack_last = nullptr;         // not owned: the pacing event of the last copy of the pinned offload
   bool twin_used[2] = {false, false};
   int64_t twin_chunks = 0;                // picks the buffer
   int last_user = 0;                      // 0 nobody yet, 1 the pinned calls, 2 the pageable calls
