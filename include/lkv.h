@@ -341,8 +341,9 @@ lkv_status lkv_set_link_gate(lkv_ctx *ctx, lkv_link_busy_fn busy, void *user, in
  * split-K workspace.  This call never allocates and never synchronises: the workspace is the one lkv_create made
  * (32 MiB: enough for 256 sequences of 16384 tokens with 32 query heads) or the one the last
  * lkv_reserve_decode_workspace made; a call that needs more returns LKV_ERR_INVALID_ARG and enqueues nothing.
- * A context has ONE workspace: split calls of one context must not run at the same time on different streams
- * (calls on one stream, or ordered by events, are fine). */
+ * A context has ONE workspace: a split call on another stream than the context's last split call is made to wait
+ * (on its stream) for that one, so calls of one context on several streams are safe, and those that split do not
+ * overlap. */
 lkv_status lkv_paged_decode_attention(lkv_ctx *ctx, int32_t layer, const void *Q, void *O,
                                       const int32_t *block_table, int32_t max_blocks_per_seq,
                                       const int32_t *context_lens, int32_t num_seqs, void *stream);

@@ -396,6 +396,11 @@ static lkv_status create_impl(const lkv_config *cfg, lkv_ctx **out, bool with_de
     return bail(LKV_ERR_DEVICE);
   }
   c->ws_bytes = kDefaultDecodeWorkspace;
+  e = hipEventCreateWithFlags(&c->ws_done, hipEventDisableTiming);
+  if (e != hipSuccess) {
+    c->err = std::string("hipEventCreate failed: ") + hipGetErrorString(e);
+    return bail(LKV_ERR_DEVICE);
+  }
   *out = c;
   return LKV_OK;
 }
@@ -421,6 +426,7 @@ void lkv_destroy(lkv_ctx *c) {
   }
   for (auto &e : c->spare_events) (void)hipEventDestroy(e);
   if (c->ws) (void)hipFree(c->ws);
+  if (c->ws_done) (void)hipEventDestroy(c->ws_done);
   if (c->owns_pool && c->pool) (void)hipFree(c->pool);
   delete c;
 }
@@ -898,10 +904,17 @@ lkv_status lkv_paged_decode_attention(lkv_ctx *c, int32_t layer, const void *Q, 
                 "the context has %lld: call lkv_reserve_decode_workspace first (this call never allocates)",
                 num_seqs, max_blocks_per_seq, (long long)need, (long long)c->ws_bytes);
   if (lkv_status st = wait_event(c, layer, LKV_EV_RELOADED, s)) return st;
+  // the context's one workspace: a split launch on another stream than the last split launch waits for that one
+  if (need > 0 && c->ws_in_use && c->ws_stream != s) LKV_HIP(c, hipStreamWaitEvent(s, c->ws_done, 0));
   hipEvent_t t0;
   if (lkv_status st = timed_begin(c, s, &t0)) return st;
   LKV_HIP(c, lkv::launch_paged_decode(c, Q, O, block_table, max_blocks_per_seq, context_lens, num_seqs, c->ws, s));
   if (lkv_status st = timed_end(c, s, t0, 0, lkv_ctx::kTimedDecode)) return st;
+  if (need > 0) {
+    LKV_HIP(c, hipEventRecord(c->ws_done, s));
+    c->ws_stream = s;
+    c->ws_in_use = true;
+  }
   c->stats.decode_calls += 1;
   return LKV_OK;
 }

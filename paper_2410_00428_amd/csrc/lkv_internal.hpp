@@ -90,9 +90,13 @@ struct lkv_ctx {
   lkv::Staging d2h, h2d;
   std::vector<hipEvent_t> events;  // [layer][4]
   std::vector<uint8_t> event_recorded;
-  // split-K workspace of decode attention
+  // split-K workspace of decode attention; ws_done is recorded behind every split launch, and a split launch on
+  // another stream than the last one waits for it (one workspace per context: two launches must not overlap)
   float *ws = nullptr;
   int64_t ws_bytes = 0;
+  hipEvent_t ws_done = nullptr;
+  hipStream_t ws_stream = nullptr;
+  bool ws_in_use = false;
   // logical state
   std::vector<int32_t> free_list;  // stack, back() is handed out next
   std::unordered_map<lkv::LayerKey, lkv::LayerState, lkv::LayerKeyHash> layers;

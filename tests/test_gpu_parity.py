@@ -354,6 +354,31 @@ def test_decode_even_split_of_launches_with_few_rows(Hq, Hkv, lens):
     sc.close()
 
 
+def test_split_decode_calls_of_one_context_on_two_streams():
+    """A context has one split-K workspace; split launches issued on two streams without any ordering between
+    them are serialised by the library (the second waits for the first's merge), so both are right."""
+    shape = wl.KVShape(1, 8, 8, 128, 16, "bf16")
+    lens = (3000, 2500, 40, 1777)
+    sc = Scenario(29, shape, lens, sum((n + 16) // 16 + 1 for n in lens) + 8)
+    sc.prefill_layer(0, check_attn=False)
+    torch.cuda.synchronize()
+    B = len(lens)
+    bt = sc.c.padded_block_table(range(B), 0)
+    ctx = np.asarray(lens, dtype=np.int32)
+    btd, cd = H.to_dev(bt), H.to_dev(ctx)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    qs = [wl.decode_qkv(29, 0, 10 + i, B, shape, 1.0, q_gain=2.0)[0] for i in range(6)]
+    qd = [H.to_dev(q) for q in qs]
+    outs = [H.empty_like_storage(qs[0].shape, "bf16") for _ in qs]
+    for i in range(6):                              # alternate streams, nothing between the calls
+        sc.c.paged_decode_attention(0, qd[i], outs[i], btd, bt.shape[1], cd, B, streams[i % 2])
+    torch.cuda.synchronize()
+    for i in range(6):
+        ref = sc.o.paged_decode_attention(qs[i], bt, ctx, threads=ORC_THREADS)
+        H.check_attention(H.to_host(outs[i], "bf16"), ref, "bf16", 1.0, f"call {i} on stream {i % 2}")
+    sc.close()
+
+
 @pytest.mark.parametrize("Hq,Hkv,lens", [(8, 2, (3000, 1111)), (8, 1, (2500,)), (4, 4, (600, 90, 1))])
 def test_decode_small_batches_get_smaller_partitions_from_the_plan(Hq, Hkv, lens):
     """With the library's own plan (no partition given) a launch of a few sequences is cut into partitions of as
