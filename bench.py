@@ -435,6 +435,8 @@ def mixed_iteration(args) -> dict:
         out["decode_other_workloads"] = decode_other_workloads(torch, dev, numbers=(3, 4, 5))
         out["decode_other_workloads"]["note"] = ("each batch's decode launches alone (a few layers in turn, nothing else on "
                                                  "the GPU); 5 is the main workload's own batch outside the iteration")
+        # the 8-bit pool (the paper's future-work direction) on workload 2's shape: write and decode over E4M3 codes
+        out["fp8_pool"] = fp8_pool_figures(torch, dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds, lens=sorted(dlens)[len(dlens) // 2 - 1:len(dlens) // 2 + 1])
     return out
