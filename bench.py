@@ -285,6 +285,48 @@ def pinned_copy_peak(torch, dev) -> dict:
     return link
 
 
+def host_memory_available() -> int:
+    """Bytes of host memory this process may still take: the smaller of the machine's MemAvailable and the room
+    left under the memory limit of its control group, when there is one."""
+    avail = None
+    try:
+        for ln in open("/proc/meminfo"):
+            if ln.startswith("MemAvailable:"):
+                avail = int(ln.split()[1]) * 1024
+    except OSError:
+        pass
+    for lim, cur in (("/sys/fs/cgroup/memory.max", "/sys/fs/cgroup/memory.current"),
+                     ("/sys/fs/cgroup/memory/memory.limit_in_bytes", "/sys/fs/cgroup/memory/memory.usage_in_bytes")):
+        try:
+            a, b = open(lim).read().strip(), open(cur).read().strip()
+            if a.isdigit() and int(a) < (1 << 60):
+                room = int(a) - int(b)
+                avail = room if avail is None else min(avail, room)
+        except OSError:
+            pass
+    return avail if avail is not None else 1 << 62
+
+
+def fit_decode_seqs(args) -> int:
+    """Workload 5 keeps 24 of 32 layers of its decode batch in ordinary host memory (211 GiB at 64 sequences).  On a
+    machine that cannot hold that, the batch is cut to the largest number of sequences whose images fit (with 24 GiB
+    left for everything else); the line then says so in `config.workload`."""
+    from paper_2410_00428_amd import workloads as wl
+    asked, avail = args.decode_seqs, host_memory_available()
+    n = asked
+    while n > 4:
+        w = wl.workload(5, decode_seqs_cfg5=n)
+        blocks = sum(wl.blocks_for(t, w.shape.block_size) for t in w.decode_lens)
+        per_block = w.shape.block_bytes // (2 if args.kv_dtype == "fp8" else 1)
+        if len(w.offload_layers) * blocks * per_block + (24 << 30) <= avail:
+            break
+        n -= 4
+    if n != asked:
+        print(f"[bench workload 5] host memory available {avail / 2**30:.0f} GiB: decode batch cut from {asked} to {n} "
+              f"sequences", file=sys.stderr, flush=True)
+    return n
+
+
 def mixed_iteration(args) -> dict:
     """Workload 5 at its full size: 64 decoding sequences (contexts uniform in [128, 16384], ~8 GiB of KV per
     layer) of which 24 of 32 layers live in ORDINARY host memory (~194 GiB) and come back through a ring of
@@ -298,6 +340,8 @@ def mixed_iteration(args) -> dict:
     def say(msg):
         print(f"[bench workload 5] {msg}", file=sys.stderr, flush=True)
 
+    asked_seqs = args.decode_seqs
+    args.decode_seqs = fit_decode_seqs(args)
     w = wl.workload(5, decode_seqs_cfg5=args.decode_seqs)
     kw = {}
     if args.kv_dtype == "fp8":   # the same iteration over an 8-bit pool: every image and every reload is half as large
@@ -393,7 +437,9 @@ def mixed_iteration(args) -> dict:
                                f"{B} decoding sequences with contexts {min(dlens)}..{max(dlens)} ({Td} tokens), "
                                f"{len(host)} of {L} layers of them in ordinary host memory and reloaded through a ring of "
                                f"{R} sets of blocks, {len(plens)} new prompts x {plens[0]} tokens prefilled and offloaded "
-                               f"in the same iteration)",
+                               f"in the same iteration)"
+                               + (f"; DEVIATION: the decode batch is cut from {asked_seqs} sequences because the host "
+                                  f"memory of this machine cannot hold their images" if B != asked_seqs else ""),
                    "value_is": "decode paged attention: context KV bytes / HIP-event time of the decode launches "
                                "(library events), measured inside the iteration"},
         "components": {
@@ -429,7 +475,9 @@ def mixed_iteration(args) -> dict:
     import gc
     gc.collect()
     torch.cuda.empty_cache()
-    out["roofline"]["traffic"] = measured_traffic("paged_decode_mfma_kernel", 5) if args.kv_dtype == "bf16" else None
+    # the counters were read at the full batch of 64 sequences
+    out["roofline"]["traffic"] = (measured_traffic("paged_decode_mfma_kernel", 5)
+                                  if args.kv_dtype == "bf16" and B == 64 else None)
     if not args.no_extras:
         # the decode batches of the other configurations (the 70B-shaped GQA batch of workload 4 among them)
         out["decode_other_workloads"] = decode_other_workloads(torch, dev, numbers=(3, 4, 5))

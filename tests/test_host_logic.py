@@ -233,3 +233,30 @@ def test_header_is_plain_c_and_the_library_links_and_runs_from_c(tmp_path):
     assert r.returncode == 0, r.stderr
     r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
     assert r.returncode == 0 and "c_abi_check: ok" in r.stdout, r.stdout + r.stderr
+
+
+def test_bench_cuts_the_workload_5_batch_to_the_host_memory_there_is(monkeypatch):
+    """The default bench line keeps 211 GiB of layer images in host memory; on a smaller machine it must shrink the
+    decode batch (and say so) rather than be killed."""
+    import types
+    import bench
+
+    def images(n, fp8=False):
+        w = wl.workload(5, decode_seqs_cfg5=n)
+        blocks = sum(wl.blocks_for(t, w.shape.block_size) for t in w.decode_lens)
+        return len(w.offload_layers) * blocks * w.shape.block_bytes // (2 if fp8 else 1)
+
+    monkeypatch.setattr(bench, "host_memory_available", lambda: 1 << 62)
+    assert bench.fit_decode_seqs(types.SimpleNamespace(decode_seqs=64, kv_dtype="bf16")) == 64
+    monkeypatch.setattr(bench, "host_memory_available", lambda: 270 << 30)
+    assert bench.fit_decode_seqs(types.SimpleNamespace(decode_seqs=64, kv_dtype="bf16")) == 64
+    assert images(64) + (24 << 30) <= 270 << 30
+    for avail_gib in (200, 100, 40):
+        monkeypatch.setattr(bench, "host_memory_available", lambda a=avail_gib: a << 30)
+        n = bench.fit_decode_seqs(types.SimpleNamespace(decode_seqs=64, kv_dtype="bf16"))
+        assert 4 <= n < 64 and n % 4 == 0
+        assert images(n) + (24 << 30) <= avail_gib << 30 or n == 4
+        assert images(n + 4) + (24 << 30) > avail_gib << 30
+    monkeypatch.setattr(bench, "host_memory_available", lambda: 150 << 30)
+    assert bench.fit_decode_seqs(types.SimpleNamespace(decode_seqs=64, kv_dtype="fp8")) == 64   # half-size images
+    assert bench.host_memory_available() > 0
