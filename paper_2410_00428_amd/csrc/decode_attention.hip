@@ -862,16 +862,17 @@ Plan make_plan(const lkv_ctx *c, int num_seqs, int max_blocks) {
   static int cus = 0;
   if (cus == 0 && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess) cus = 256;
   p.lpt = p.mfma && num_seqs <= 256 && units * p.num_parts <= (int64_t)8 * cus;
-  // A split launch with FEW rows (sequences x kv heads) ends when its largest item ends, and its partitions have to
-  // be small to give every CU something, which multiplies the per-workgroup start-up and the merge work.  Such
-  // launches are cut evenly instead: one workgroup per CU, every one with the same share of the launch's key pairs
-  // (kOrderEven).  Measured on MI355X, partitioned -> even: one 16384-token context of the 70B shape 31 -> 26 us, of
-  // the 7B shape 71 -> 57 us, four 8192-token contexts of the 70B shape 42 -> 35 us.  From about half a row per CU
-  // on, the partitioned launch with its dynamic order is as good or better (16 ragged contexts x 8 kv heads: 87.5
-  // against 90 us; 4 x 16385 tokens x 32 heads: 195 either way): equal shares end with the slowest CU, while
-  // workgroups handed out as CUs become free even out the CUs' unequal rates.  A partition size set by the caller
-  // keeps the partitioned launch.
-  if (p.lpt && p.num_parts > 1 && c->cfg.decode_partition == 0 && num_seqs <= kMaxEvenSeqs && units * 8 <= (int64_t)cus * 3 &&
+  // A split launch is cut evenly instead of into partitions of a fixed size: one workgroup per CU, every one with the
+  // same share of the launch's key pairs (kOrderEven), whatever the contexts' lengths.  A partitioned launch ends
+  // when the CU with the largest items ends, pays the start-up and the merge once per partition, and needs small
+  // partitions to give every CU something when the rows (sequences x kv heads) are few.  Measured on MI355X,
+  // partitioned -> even: one 16384-token context of the 70B shape 31 -> 26 us, four 8192-token contexts of it
+  // 42 -> 35 us; ragged batches (contexts uniform in 128..16384) of the 70B shape with 16 / 64 / 128 / 256 sequences
+  // 87.8 -> 84.1 / 452 -> 408 / 752 -> 658 / 1490 -> 1359 us, of the 7B shape with 4 / 16 / 32 / 64 sequences
+  // 85 -> 80 / 282 -> 274 / 822 -> 796 / 1519 -> 1479 us; 4 x 16385 tokens x 32 heads 180 either way; the worst
+  // case seen is 3 % behind (48 ragged sequences of the 7B shape).  A partition size set by the caller keeps the
+  // partitioned launch, and so do batches of more than kMaxEvenSeqs sequences.
+  if (p.mfma && p.num_parts > 1 && c->cfg.decode_partition == 0 && num_seqs <= kMaxEvenSeqs &&
       units * (tokens / (2 * kBlock) + 1 + kRowCost) < ((int64_t)1 << 30)) {
     p.even_wgs = cus < 1024 ? cus : 1024;  // the merge kernel keeps one weight per workgroup in LDS
     p.waves = 8;

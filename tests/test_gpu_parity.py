@@ -323,13 +323,15 @@ def test_decode_ragged_batches_longest_first_work_list(B, Hq, Hkv, max_len):
 
 
 MANY_SHORT = tuple(int(x) for x in np.random.default_rng(77).integers(1, 400, size=89)) + (5000,)
+MANY_ROWS = tuple(int(x) for x in np.random.default_rng(78).integers(1, 9000, size=48))   # 384 rows: more than CUs
 
 
 @pytest.mark.parametrize("Hq,Hkv,lens", [(8, 8, (5000, 31, 640, 700, 33, 4097, 1)), (64, 8, (16384, 100)),
-                                         (32, 2, (900, 2000, 17)), (4, 1, (9000,)), (4, 1, MANY_SHORT)])
+                                         (32, 2, (900, 2000, 17)), (4, 1, (9000,)), (4, 1, MANY_SHORT),
+                                         (8, 8, MANY_ROWS)])
 def test_decode_even_split_of_launches_with_few_rows(Hq, Hkv, lens):
-    """A split launch with few (sequence, kv head) rows is cut into equal shares of key pairs, one per CU, whatever
-    rows they belong to: rows cut by several workgroups, workgroups that hold several short rows, rows that end on
+    """A split launch is cut into equal shares of key pairs, one per CU, whatever (sequence, kv head) rows they
+    belong to, with few rows or with more rows than CUs: rows cut by several workgroups, workgroups that hold several short rows, rows that end on
     a pair boundary or in the middle of a block, one to sixteen query heads per kv head, ninety sequences (the
     running sums take two rounds of 64).  Then the same launch with
     contexts cut to zero, to one token and to a block boundary (the shares move, empty rows give zero rows)."""
@@ -500,9 +502,11 @@ def test_prefill_stays_inside_its_tensors_whatever_cu_seqlens_holds(shape):
 def test_decode_never_allocates_and_reserve_grows_the_workspace():
     """lkv_paged_decode_attention uses the workspace the context has: a launch that needs more is refused with an
     error that names lkv_reserve_decode_workspace, and runs once that call has made room.  The host sizes the split
-    from the table WIDTH, so wide tables over a small pool are enough to need more than the 32 MiB of lkv_create."""
+    from the table WIDTH, so wide tables over a small pool are enough to need more than the 32 MiB of lkv_create:
+    320 sequences (more than an evenly cut launch takes, so fixed partitions) x 64 heads x 4 partitions x 130 floats
+    = 41 MiB."""
     shape = wl.KVShape(1, 64, 8, 128, 16, "bf16")
-    B, width, nblk = 256, 1024, 64
+    B, width, nblk = 320, 1024, 64
     sc = Scenario(33, shape, (200, 90), nblk)
     sc.prefill_layer(0, check_attn=False)
     rows = [sc.c.get_block_table(s % 2, 0) for s in range(B)]

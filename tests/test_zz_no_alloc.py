@@ -61,8 +61,9 @@ def test_static_scratch_decode_is_really_split_and_rejects_what_does_not_fit():
     torch.cuda.synchronize()
     ref = sc.o.paged_decode_attention(q, bt, ctx, threads=ORC_THREADS)
     H.check_attention(H.to_host(O1, "bf16"), ref, "bf16", 1.0, "64-token partitions through the fixed scratch")
-    # 128 sequences x 64 heads x 1024-block tables (4 partitions) x 130 floats = 17 MiB > 8 MiB
-    B, width = 128, 1024
+    # 272 sequences (more than an evenly cut launch takes: partitions) x 64 heads x 512-block tables (2 partitions)
+    # x 130 floats = 17 MiB > 8 MiB
+    B, width = 272, 512
     wide = np.full((B, width), -1, dtype=np.int32)
     wide[:, :bt.shape[1]] = bt[0]
     qq = wl.normal_tensor(np.random.default_rng(4), (B, 64, 128), 1.0, "bf16")
