@@ -336,9 +336,10 @@ lkv_status lkv_set_link_gate(lkv_ctx *ctx, lkv_link_busy_fn busy, void *user, in
  * kernels clamp an entry outside [0, num_pool_blocks) into the pool, which gives a wrong row but touches no memory
  * outside the pool); context_lens: device, int32[num_seqs] (a value above 16*max_blocks_per_seq is cut there);
  * sequence s attends to positions 0..context_lens[s]-1; a zero context gives a zero row.
- * Waits (on `stream`) for LKV_EV_RELOADED of the layer.  Long contexts are split into
- * partitions whose partial results are merged by a second kernel; the partial results go through the context's
- * split-K workspace.  This call never allocates and never synchronises: the workspace is the one lkv_create made
+ * Waits (on `stream`) for LKV_EV_RELOADED of the layer.  A launch with long contexts (or with too few sequences to
+ * fill the GPU) is split: cut into equal shares of its keys, one per compute unit, or, when decode_partition is set
+ * or the batch has more than 256 sequences, into partitions of a fixed number of tokens; a second kernel merges the
+ * partial results, which go through the context's split-K workspace.  This call never allocates and never synchronises: the workspace is the one lkv_create made
  * (32 MiB: enough for 256 sequences of 16384 tokens with 32 query heads) or the one the last
  * lkv_reserve_decode_workspace made; a call that needs more returns LKV_ERR_INVALID_ARG and enqueues nothing.
  * A context has ONE workspace: a split call on another stream than the context's last split call is made to wait
@@ -357,8 +358,9 @@ lkv_status lkv_reserve_decode_workspace(lkv_ctx *ctx, int32_t num_seqs, int32_t 
  * forbid hipMalloc): the same operation, arguments, kernels and results as lkv_paged_decode_attention, with the
  * split-K partial results in a fixed array that is part of the library's device code (8 MiB per GPU, held until the
  * process ends) instead of the context's workspace.  Calls no hipMalloc / hipFree and creates nothing.  A call whose
- * partial results exceed the array (num_seqs * num_q_heads * partitions * (head_dim + 2) * 4 bytes > 8 MiB) returns
- * LKV_ERR_INVALID_ARG and enqueues nothing.  Kernel profiling (lkv_set_profiling) does not cover this call.  Every
+ * partial results exceed the array ((head_dim + 2) * 4 bytes for each of num_seqs * num_q_heads * partitions entries
+ * of a partitioned launch, or of (num_seqs * num_kv_heads + compute units) * (num_q_heads / num_kv_heads) entries
+ * of an evenly cut one, > 8 MiB) returns LKV_ERR_INVALID_ARG and enqueues nothing.  Kernel profiling (lkv_set_profiling) does not cover this call.  Every
  * call on a GPU, from any context, uses that GPU's one array: calls that overlap in time on one GPU (two streams
  * without an event between them) race on it; each call overwrites what it reads, so nothing needs clearing between
  * calls. */
